@@ -1,0 +1,173 @@
+#!/usr/bin/env python3
+"""Benchmark of the speculative-decoding hot path on one MI355X.
+
+One "step" is one draft + verify + accept cycle (all hot-path stages) at batch 1, T = 0, on a
+synthetic random-init LLaMA2-7B-shaped model (bf16, prompt 512, dynamic tree depth 6 / top-k 10 /
+60 verified tokens).  Prints ONE JSON line: tokens/s over exactly --steps cycles, the roofline of the
+dominant kernel (the weight-streaming GEMM, timed with HIP events in a separate instrumented pass),
+and the CPU oracle timed on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=64)
+    ap.add_argument("--warmup", type=int, default=4)
+    ap.add_argument("--config", default="llama2-7b", help="workload name (see workload.CONFIGS)")
+    ap.add_argument("--layers", type=int, default=0, help="override the number of target layers (0 = the config's)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-roofline-pass", action="store_true", help="skip the instrumented passes (for profilers)")
+    return ap.parse_args()
+
+
+def run_cycles(eng, n_cycles):
+    emitted = 0
+    for _ in range(n_cycles):
+        t = eng.draft_tree()
+        eng.verify(t)
+        emitted += len(eng.accept(t))
+    return emitted
+
+
+def cpu_baseline(sh, layers_timed=2):
+    """The oracle as it stands, on the host cores: one draft+verify+accept cycle of a depth-truncated model
+    (same widths, same prompt length), plus one decoder layer over the tree rows to extrapolate to full depth."""
+    import numpy as np
+    import workload as wl
+    import oracle
+    from oracle.llama import as_dtype
+    tsh = sh.with_(n_layers=layers_timed)
+    w = as_dtype(wl.make_weights(tsh), np.float32)
+    prompt = wl.make_prompt(tsh)
+    st, _ = oracle.prefill(w, tsh, prompt, len(prompt) + 256, dtype=np.float32)
+    t0 = time.perf_counter()
+    st.cycle = 1
+    tree = oracle.draft_tree(st, tsh.tree_depth, tsh.tree_topk, tsh.tree_total)
+    t1 = time.perf_counter()
+    logits, feats = oracle.verify_tree(st, tree)
+    acc, bonus = oracle.accept_greedy(tree, logits)
+    emitted = oracle.commit(st, tree, feats, acc, bonus)
+    t2 = time.perf_counter()
+    # one more layer over the same rows, to extrapolate linearly in depth
+    n = st.n - len(emitted)                                   # the verified rows still sit at slots n + j
+    rows = tree.n_nodes
+    h = np.random.default_rng(0).standard_normal((rows, tsh.d_model)).astype(np.float32)
+    vis = [list(range(n)) + [n + a for a in tree.path(j)] for j in range(rows)]
+    t3 = time.perf_counter()
+    oracle.decoder_layer(h, w, "layers.0.", tsh, 0, st.tcache, (n + tree.depth).astype(np.int64),
+                         [n + j for j in range(rows)], vis)
+    t4 = time.perf_counter()
+    draft_s, verify_s, layer_s = t1 - t0, t2 - t1, t4 - t3
+    full_cycle = draft_s + verify_s + (sh.n_layers - layers_timed) * layer_s
+    return {
+        "value": len(emitted) / full_cycle, "unit": "tokens/s", "cores": os.cpu_count(), "kind": "oracle",
+        "sample": f"1 cycle on a {layers_timed}-layer truncation at full width (draft {draft_s:.2f} s, verify {verify_s:.2f} s), "
+                  f"extrapolated to {sh.n_layers} layers with one timed decoder layer ({layer_s:.2f} s); numpy fp32",
+        "measured_truncated_cycle_s": draft_s + verify_s,
+    }
+
+
+def main():
+    a = parse()
+    if a.gpus != 1:
+        print("bench.py: this build runs on one GPU only (batch-1 decode has no data-parallel units); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+    import torch
+    import workload as wl
+    import paper_2408_15766_amd as P
+
+    sh = wl.BY_NAME[a.config]
+    if a.layers:
+        sh = sh.with_(n_layers=a.layers, name=f"{sh.name}-{a.layers}layer")
+    torch.cuda.set_device(0)
+    weights = dict(wl.iter_device_weights(sh, "cuda"))
+    prompt = wl.make_prompt(sh)
+    total_cycles = a.warmup + a.steps
+    max_seq = sh.prompt_len + (sh.tree_depth + 1) * total_cycles + sh.tree_total + 32
+
+    # ---- pass A: the timed region ------------------------------------------------------------
+    eng = P.Engine(sh, weights, max_seq=max_seq)
+    eng.prefill(prompt)
+    run_cycles(eng, a.warmup)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    emitted = run_cycles(eng, a.steps)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    eng.close()
+    tokens_per_s = emitted / dt
+    ms_per_step = dt / a.steps * 1e3
+
+    # plain autoregressive decoding through the same kernels (tree = the root alone): the 1.00x reference
+    plain = P.Engine(sh, weights, max_seq=max_seq, tree=(1, 1, 1))
+    plain.prefill(prompt)
+    run_cycles(plain, a.warmup)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    pe = run_cycles(plain, a.steps)
+    torch.cuda.synchronize()
+    plain_dt = time.perf_counter() - t0
+    plain.close()
+
+    by = wl.algorithmic_bytes(sh)
+    n_mid = sh.prompt_len + a.warmup + a.steps // 2
+    kv_read = n_mid * by["kv_bytes_per_token"]
+    kv_write = sh.tree_total * by["kv_bytes_per_token"]
+    out = {
+        "metric": "tokens/s (bs=1, T=0)", "value": tokens_per_s, "unit": "tokens/s", "n_gpus": 1, "steps": a.steps,
+        "warmup": a.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": sh.dtype, "data": "synthetic",
+        "config": {"workload": f"{sh.name} shape, random init N(0,0.02), prompt {sh.prompt_len} uniform tokens, "
+                               f"tree depth {sh.tree_depth} top-k {sh.tree_topk} total {sh.tree_total}, T=0, batch 1"},
+        "ms_per_cycle": ms_per_step,
+        "mean_accepted_length": emitted / a.steps,
+        "plain_decode_tokens_per_s": pe / plain_dt,
+        "plain_decode_ms_per_token": plain_dt / a.steps * 1e3,
+    }
+
+    # ---- pass B / C: instrumented with HIP events on the library's stream ---------------------
+    if not a.no_roofline_pass:
+        for level in (1, 2):
+            eng = P.Engine(sh, weights, max_seq=max_seq)
+            eng.prefill(prompt)
+            run_cycles(eng, a.warmup)
+            P.spec_set_profile(eng.ctx, level)
+            run_cycles(eng, a.steps)
+            ms, cnt = P.spec_get_profile(eng.ctx)
+            eng.close()
+            if level == 1:
+                draft_ms, verify_ms, accept_ms = (ms[i] / max(cnt[i], 1) for i in range(3))
+                out.update({"draft_ms": draft_ms, "verify_ms": verify_ms, "accept_ms": accept_ms,
+                            "verify_hbm_gbps": (by["verify_weights"] + kv_read + kv_write) / (verify_ms * 1e-3) / 1e9,
+                            "verify_hbm_frac": (by["verify_weights"] + kv_read + kv_write) / (verify_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS})
+            else:
+                n_launch = cnt[4] / a.steps                      # GEMM launches per verify
+                avg_ms = ms[4] / max(cnt[4], 1)
+                bytes_per_launch = by["verify_weights"] / n_launch
+                achieved = bytes_per_launch / (avg_ms * 1e-3) / 1e9
+                out["roofline"] = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                                   "frac": achieved / HBM_PEAK_GBPS, "traffic": None,
+                                   "kernel": "gemm_stream_kernel (verify launches)", "launches_per_step": n_launch,
+                                   "avg_launch_ms": avg_ms, "algorithmic_bytes_per_launch": bytes_per_launch}
+    if not a.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(wl.BY_NAME[a.config])
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -66,21 +66,32 @@ def attention_row(q: np.ndarray, keys: np.ndarray, vals: np.ndarray) -> np.ndarr
     return p @ vals
 
 
+def _identity(x: np.ndarray) -> np.ndarray:
+    return x
+
+
 def decoder_layer(h: np.ndarray, w: Weights, prefix: str, shape, layer_idx: int, cache: KVCache,
-                  pos: np.ndarray, slots: Sequence[int], visible: Sequence[Sequence[int]]) -> np.ndarray:
+                  pos: np.ndarray, slots: Sequence[int], visible: Sequence[Sequence[int]], store=_identity) -> np.ndarray:
     """One pre-norm decoder layer over `rows` inputs.
 
     Row i is at position pos[i]; its key/value are written to cache slot slots[i];
     it attends to the cache slots visible[i] (which must include slots[i]).
+
+    `store` models the configuration's storage type: it is applied to every
+    tensor that is held in memory between two operations (norm outputs, cached
+    keys and values, the attention output, the SwiGLU output).  The residual
+    stream, the queries and all accumulations stay in the compute dtype.  The
+    default is the identity (the plain definition); a bf16 configuration may
+    pass a round-to-bf16 function to ask what a bf16-storage pipeline computes.
     """
     rows = h.shape[0]
     hq, hkv, hd = shape.n_q_heads, shape.n_kv_heads, shape.head_dim
-    a = rmsnorm(h, w[prefix + "attn_norm"], shape.rms_eps)
+    a = store(rmsnorm(h, w[prefix + "attn_norm"], shape.rms_eps))
     q = (a @ w[prefix + "wq"].T).reshape(rows, hq, hd)
     k = (a @ w[prefix + "wk"].T).reshape(rows, hkv, hd)
-    v = (a @ w[prefix + "wv"].T).reshape(rows, hkv, hd)
+    v = store((a @ w[prefix + "wv"].T).reshape(rows, hkv, hd))
     q = rope(q, pos, shape.rope_theta)
-    k = rope(k, pos, shape.rope_theta)
+    k = store(rope(k, pos, shape.rope_theta))
     for i in range(rows):
         cache.k[layer_idx, slots[i]] = k[i]
         cache.v[layer_idx, slots[i]] = v[i]
@@ -91,32 +102,32 @@ def decoder_layer(h: np.ndarray, w: Weights, prefix: str, shape, layer_idx: int,
         for hh in range(hq):
             kvh = hh // group
             att[i, hh] = attention_row(q[i, hh], cache.k[layer_idx, vis, kvh], cache.v[layer_idx, vis, kvh])
-    h = h + att.reshape(rows, hq * hd) @ w[prefix + "wo"].T
-    b = rmsnorm(h, w[prefix + "ffn_norm"], shape.rms_eps)
+    h = h + store(att.reshape(rows, hq * hd)) @ w[prefix + "wo"].T
+    b = store(rmsnorm(h, w[prefix + "ffn_norm"], shape.rms_eps))
     g = b @ w[prefix + "w_gate"].T
     u = b @ w[prefix + "w_up"].T
-    act = g / (1.0 + np.exp(-g)) * u
+    act = store(g / (1.0 + np.exp(-g)) * u)
     return h + act @ w[prefix + "w_down"].T
 
 
 def target_forward(w: Weights, shape, cache: KVCache, tokens: np.ndarray, pos: np.ndarray,
-                   slots: Sequence[int], visible: Sequence[Sequence[int]]):
+                   slots: Sequence[int], visible: Sequence[Sequence[int]], store=_identity):
     """Target LLM over rows -> (logits [rows, V], features [rows, d])."""
     h = w["embed"][np.asarray(tokens, dtype=np.int64)].astype(cache.k.dtype)
     for l in range(shape.n_layers):
-        h = decoder_layer(h, w, f"layers.{l}.", shape, l, cache, pos, slots, visible)
-    f = rmsnorm(h, w["final_norm"], shape.rms_eps)
+        h = decoder_layer(h, w, f"layers.{l}.", shape, l, cache, pos, slots, visible, store)
+    f = store(rmsnorm(h, w["final_norm"], shape.rms_eps))
     return f @ w["lm_head"].T, f
 
 
 def draft_forward(w: Weights, shape, dcache: KVCache, feats: np.ndarray, tokens: np.ndarray, pos: np.ndarray,
-                  slots: Sequence[int], visible: Sequence[Sequence[int]]):
+                  slots: Sequence[int], visible: Sequence[Sequence[int]], store=_identity):
     """Draft model over rows of (previous-position feature, current token).
 
     -> (draft logits [rows, V], predicted features g [rows, d])."""
     e = w["embed"][np.asarray(tokens, dtype=np.int64)].astype(dcache.k.dtype)
     z = np.concatenate([feats.astype(dcache.k.dtype), e], axis=-1) @ w["draft.fc"].T
-    g = decoder_layer(z, w, "draft.", shape, 0, dcache, pos, slots, visible)
+    g = store(decoder_layer(z, w, "draft.", shape, 0, dcache, pos, slots, visible, store))
     return g @ w["lm_head"].T, g
 
 

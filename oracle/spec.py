@@ -81,6 +81,7 @@ class SpecState:
     pend_tokens: Optional[np.ndarray] = None  # [m+1] tokens at positions n-m .. n (last one is the root)
     cycle: int = 0
     g_root: Optional[np.ndarray] = None
+    store: Callable = None            # storage-type model handed to the forwards (None = identity)
 
 
 # --------------------------------------------------------------------------- definition layer
@@ -121,17 +122,22 @@ def sample_decode(w: Weights, shape, prompt: np.ndarray, gen: int, temperature: 
 
 # --------------------------------------------------------------------------- algorithm layer
 
+def _kw(st_or_store):
+    store = st_or_store.store if isinstance(st_or_store, SpecState) else st_or_store
+    return {} if store is None else {"store": store}
+
+
 def prefill(w: Weights, shape, prompt: np.ndarray, max_seq: int, temperature: float = 0.0, seed: int = 0,
-            dtype=np.float64) -> Tuple[SpecState, int]:
+            dtype=np.float64, store=None) -> Tuple[SpecState, int]:
     """Target forward over the prompt, first token, and the draft over the prompt pairs.
 
     reading: pair i = (target feature of position i-1, token at position i) sits
     at rotary position i and predicts the feature of position i."""
     n = len(prompt)
     st = SpecState(w, shape, KVCache(shape.n_layers, max_seq, shape.n_kv_heads, shape.head_dim, dtype),
-                   KVCache(1, max_seq, shape.n_kv_heads, shape.head_dim, dtype))
+                   KVCache(1, max_seq, shape.n_kv_heads, shape.head_dim, dtype), store=store)
     logits, feats = target_forward(w, shape, st.tcache, prompt, np.arange(n), list(range(n)),
-                                   [list(range(i + 1)) for i in range(n)])
+                                   [list(range(i + 1)) for i in range(n)], **_kw(st))
     last = logits[-1].astype(np.float32)
     if temperature > 0:
         first = argmax_low(last / np.float32(temperature) + _rng.gumbel(seed, 0, 0, shape.vocab))
@@ -139,7 +145,8 @@ def prefill(w: Weights, shape, prompt: np.ndarray, max_seq: int, temperature: fl
         first = argmax_low(last)
     if n > 1:
         pos = np.arange(1, n)
-        draft_forward(w, shape, st.dcache, feats[:-1], prompt[1:], pos, list(pos), [list(range(1, p + 1)) for p in pos])
+        draft_forward(w, shape, st.dcache, feats[:-1], prompt[1:], pos, list(pos), [list(range(1, p + 1)) for p in pos],
+                      **_kw(st))
     st.n, st.root = n, first
     st.pend_feats = feats[-1:].copy()
     st.pend_tokens = np.array([first], dtype=np.int32)
@@ -153,7 +160,7 @@ def draft_tree(st: SpecState, depth: int, topk: int, total: int) -> Tree:
     m1 = len(st.pend_tokens)
     pos = np.arange(n - m1 + 1, n + 1)
     logits, g = draft_forward(w, shape, st.dcache, st.pend_feats, st.pend_tokens, pos, list(pos),
-                              [list(range(1, p + 1)) for p in pos])
+                              [list(range(1, p + 1)) for p in pos], **_kw(st))
     st.g_root = g[-1]
     lp = log_softmax(logits[-1]).astype(np.float32)
     pool_tok: List[int] = []
@@ -178,7 +185,7 @@ def draft_tree(st: SpecState, depth: int, topk: int, total: int) -> Tree:
             while a >= 0:
                 anc.append(slot_of[a]); a = pool_par[a]
             slots.append(slot_of[c]); vis.append(list(range(1, n + 1)) + anc[::-1])
-        logits, g = draft_forward(w, shape, st.dcache, feats, toks, np.full(rows, n + t - 1), slots, vis)
+        logits, g = draft_forward(w, shape, st.dcache, feats, toks, np.full(rows, n + t - 1), slots, vis, **_kw(st))
         lp = log_softmax(logits).astype(np.float32)
         first_child = len(pool_tok)
         for r, c in enumerate(frontier):
@@ -207,7 +214,7 @@ def verify_tree(st: SpecState, tree: Tree):
     n = st.n
     rows = tree.n_nodes
     vis = [list(range(n)) + [n + a for a in tree.path(j)] for j in range(rows)]
-    return target_forward(st.w, st.shape, st.tcache, tree.token, n + tree.depth, [n + j for j in range(rows)], vis)
+    return target_forward(st.w, st.shape, st.tcache, tree.token, n + tree.depth, [n + j for j in range(rows)], vis, **_kw(st))
 
 
 def accept_greedy(tree: Tree, logits: np.ndarray) -> Tuple[List[int], int]:
@@ -278,7 +285,7 @@ def commit(st: SpecState, tree: Tree, feats: np.ndarray, accepted: Sequence[int]
 
 
 def spec_decode(w: Weights, shape, prompt: np.ndarray, gen: int, *, depth=None, topk=None, total=None,
-                temperature: float = 0.0, seed: int = 0, dtype=np.float64,
+                temperature: float = 0.0, seed: int = 0, dtype=np.float64, store=None,
                 tree_hook: Optional[Callable[[SpecState, Tree], Tree]] = None, record: Optional[list] = None):
     """Whole run: prefill, then draft / verify / accept cycles until `gen` tokens.
 
@@ -287,7 +294,7 @@ def spec_decode(w: Weights, shape, prompt: np.ndarray, gen: int, *, depth=None, 
     topk = shape.tree_topk if topk is None else topk
     total = shape.tree_total if total is None else total
     max_seq = len(prompt) + gen + total + depth * topk + depth + 4
-    st, first = prefill(w, shape, prompt, max_seq, temperature, seed, dtype)
+    st, first = prefill(w, shape, prompt, max_seq, temperature, seed, dtype, store)
     out, taus = [first], []
     while len(out) < gen:
         st.cycle += 1

@@ -1,0 +1,11 @@
+"""MI355X-native speculative decoding with a dynamic draft tree (the decode path of HASS / EAGLE-2).
+
+The product is libspec.so (hand-written gfx950 kernels behind a C ABI, see include/spec.h); this
+package is the thin ctypes binding over it.  Importing the binding without a built library raises.
+"""
+from .binding import (Engine, SpecError, Tree, lib, spec_accept, spec_committed, spec_create, spec_destroy, spec_draft_tree,
+                      spec_get_features, spec_get_kv, spec_get_logits, spec_get_profile, spec_k_attention, spec_k_gemm,
+                      spec_k_topk_logprob, spec_last_error, spec_prefill, spec_set_profile, spec_verify, spec_workspace_bytes,
+                      upload_weights)
+
+__all__ = [n for n in dir() if not n.startswith("_")]

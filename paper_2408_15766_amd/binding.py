@@ -1,0 +1,349 @@
+"""ctypes binding of libspec.so: same names as the C ABI, argument marshalling only.
+
+torch is used for device memory (weights, the workspace) and for the current HIP stream; no
+arithmetic of the decode path happens in Python.  There is no CPU fallback: if the library has not
+been built, importing this module raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import dataclasses
+import os
+from typing import Dict, List, Optional, Sequence
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libspec.so")
+if not os.path.exists(_LIB_PATH):
+    raise ImportError(f"{_LIB_PATH} is missing: build it with `python -m paper_2408_15766_amd.build` "
+                      "(there is no fallback path)")
+lib = C.CDLL(_LIB_PATH)
+
+SPEC_OK, SPEC_EINVAL, SPEC_ESTATE, SPEC_ECAP, SPEC_EHIP = 0, -1, -2, -3, -4
+SPEC_MAX_DEPTH, SPEC_MAX_TOPK, SPEC_MAX_NODES = 15, 16, 128
+LAYER_FIELDS = ("attn_norm", "wq", "wk", "wv", "wo", "ffn_norm", "w_gate", "w_up", "w_down")
+
+
+class SpecError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"libspec error {code}: {msg}")
+        self.code = code
+
+
+class spec_config(C.Structure):
+    _fields_ = [("n_layers", C.c_int32), ("d_model", C.c_int32), ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32),
+                ("head_dim", C.c_int32), ("d_ffn", C.c_int32), ("vocab", C.c_int32),
+                ("rope_theta", C.c_float), ("rms_eps", C.c_float), ("dtype", C.c_int32), ("max_seq", C.c_int32),
+                ("tree_depth", C.c_int32), ("tree_topk", C.c_int32), ("tree_total", C.c_int32),
+                ("temperature", C.c_float), ("seed", C.c_uint64), ("device", C.c_int32), ("stream", C.c_void_p),
+                ("workspace", C.c_void_p), ("workspace_bytes", C.c_uint64)]
+
+
+class spec_layer_weights(C.Structure):
+    _fields_ = [(f, C.c_void_p) for f in LAYER_FIELDS]
+
+
+class spec_weights(C.Structure):
+    _fields_ = [("embed", C.c_void_p), ("lm_head", C.c_void_p), ("final_norm", C.c_void_p),
+                ("layers", C.POINTER(spec_layer_weights)), ("draft_fc", C.c_void_p), ("draft_layer", spec_layer_weights)]
+
+
+class spec_tree(C.Structure):
+    _fields_ = [("n_nodes", C.c_int32), ("token", C.POINTER(C.c_int32)), ("parent", C.POINTER(C.c_int32)),
+                ("depth", C.POINTER(C.c_int32)), ("score", C.POINTER(C.c_float))]
+
+
+_i32p, _f32p = C.POINTER(C.c_int32), C.POINTER(C.c_float)
+lib.spec_workspace_bytes.restype = C.c_uint64
+lib.spec_workspace_bytes.argtypes = [C.POINTER(spec_config)]
+lib.spec_create.argtypes = [C.POINTER(spec_config), C.POINTER(spec_weights), C.POINTER(C.c_void_p)]
+lib.spec_prefill.argtypes = [C.c_void_p, _i32p, C.c_int32, _i32p]
+lib.spec_draft_tree.argtypes = [C.c_void_p, C.POINTER(spec_tree)]
+lib.spec_verify.argtypes = [C.c_void_p, C.POINTER(spec_tree)]
+lib.spec_accept.argtypes = [C.c_void_p, C.POINTER(spec_tree), _i32p, _i32p]
+lib.spec_destroy.argtypes = [C.c_void_p]
+lib.spec_destroy.restype = None
+lib.spec_committed.argtypes = [C.c_void_p]
+lib.spec_get_logits.restype = C.c_int64
+lib.spec_get_logits.argtypes = [C.c_void_p, _f32p, C.c_int64]
+lib.spec_get_features.restype = C.c_int64
+lib.spec_get_features.argtypes = [C.c_void_p, _f32p, C.c_int64]
+lib.spec_get_kv.restype = C.c_int64
+lib.spec_get_kv.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, _f32p, _f32p, C.c_int64]
+lib.spec_set_profile.argtypes = [C.c_void_p, C.c_int32]
+lib.spec_get_profile.argtypes = [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_int64)]
+lib.spec_last_error.restype = C.c_char_p
+lib.spec_last_error.argtypes = [C.c_void_p]
+lib.spec_k_gemm.argtypes = [C.c_int32, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_int32, C.c_void_p,
+                            C.c_int32, C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p]
+lib.spec_k_attention.argtypes = [C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
+                                 C.c_int32, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p]
+lib.spec_k_topk_logprob.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
+                                    C.c_void_p, C.c_void_p]
+
+
+@dataclasses.dataclass
+class Tree:
+    """Host-side flattened draft tree (numpy views of the arrays handed to the C ABI)."""
+    token: np.ndarray
+    parent: np.ndarray
+    depth: np.ndarray
+    score: np.ndarray
+    n_nodes: int
+
+    @staticmethod
+    def empty(capacity: int) -> "Tree":
+        return Tree(np.zeros(capacity, np.int32), np.zeros(capacity, np.int32), np.zeros(capacity, np.int32),
+                    np.zeros(capacity, np.float32), 0)
+
+    def as_c(self) -> spec_tree:
+        for a in (self.token, self.parent, self.depth, self.score):
+            assert a.flags["C_CONTIGUOUS"]
+        return spec_tree(self.n_nodes, self.token.ctypes.data_as(_i32p), self.parent.ctypes.data_as(_i32p),
+                         self.depth.ctypes.data_as(_i32p), self.score.ctypes.data_as(_f32p))
+
+
+def _check(ctx, rc: int):
+    if rc < 0:
+        raise SpecError(rc, (lib.spec_last_error(ctx) or b"").decode())
+    return rc
+
+
+def spec_last_error(ctx) -> str:
+    return (lib.spec_last_error(ctx) or b"").decode()
+
+
+def spec_workspace_bytes(cfg: spec_config) -> int:
+    return int(lib.spec_workspace_bytes(C.byref(cfg)))
+
+
+def spec_create(cfg: spec_config, w: spec_weights):
+    out = C.c_void_p()
+    _check(None, lib.spec_create(C.byref(cfg), C.byref(w), C.byref(out)))
+    return out
+
+
+def spec_destroy(ctx) -> None:
+    lib.spec_destroy(ctx)
+
+
+def spec_committed(ctx) -> int:
+    return int(lib.spec_committed(ctx))
+
+
+def spec_prefill(ctx, prompt: np.ndarray) -> int:
+    p = np.ascontiguousarray(prompt, dtype=np.int32)
+    first = C.c_int32()
+    _check(ctx, lib.spec_prefill(ctx, p.ctypes.data_as(_i32p), len(p), C.byref(first)))
+    return int(first.value)
+
+
+def spec_draft_tree(ctx, tree: Tree) -> Tree:
+    t = tree.as_c()
+    _check(ctx, lib.spec_draft_tree(ctx, C.byref(t)))
+    tree.n_nodes = int(t.n_nodes)
+    return tree
+
+
+def spec_verify(ctx, tree: Tree) -> None:
+    t = tree.as_c()
+    _check(ctx, lib.spec_verify(ctx, C.byref(t)))
+
+
+def spec_accept(ctx, tree: Tree) -> List[int]:
+    t = tree.as_c()
+    out = (C.c_int32 * (SPEC_MAX_DEPTH + 1))()
+    n = C.c_int32()
+    _check(ctx, lib.spec_accept(ctx, C.byref(t), out, C.byref(n)))
+    return [int(out[i]) for i in range(n.value)]
+
+
+def spec_get_logits(ctx, n_nodes: int, vocab: int) -> np.ndarray:
+    buf = np.empty((n_nodes, vocab), dtype=np.float32)
+    _check(ctx, lib.spec_get_logits(ctx, buf.ctypes.data_as(_f32p), buf.size))
+    return buf
+
+
+def spec_get_features(ctx, n_nodes: int, d: int) -> np.ndarray:
+    buf = np.empty((n_nodes, d), dtype=np.float32)
+    _check(ctx, lib.spec_get_features(ctx, buf.ctypes.data_as(_f32p), buf.size))
+    return buf
+
+
+def spec_get_kv(ctx, which: int, layer: int, n_rows: int, d_kv: int):
+    k = np.empty((n_rows, d_kv), dtype=np.float32)
+    v = np.empty((n_rows, d_kv), dtype=np.float32)
+    _check(ctx, lib.spec_get_kv(ctx, which, layer, n_rows, k.ctypes.data_as(_f32p), v.ctypes.data_as(_f32p), k.size))
+    return k, v
+
+
+def spec_set_profile(ctx, level: int) -> None:
+    _check(ctx, lib.spec_set_profile(ctx, level))
+
+
+def spec_get_profile(ctx):
+    ms = (C.c_double * 8)()
+    cnt = (C.c_int64 * 8)()
+    _check(ctx, lib.spec_get_profile(ctx, ms, cnt))
+    return [float(x) for x in ms], [int(x) for x in cnt]
+
+
+def _stream_ptr(stream=None):
+    import torch
+    s = torch.cuda.current_stream() if stream is None else stream
+    return C.c_void_p(s.cuda_stream)
+
+
+def spec_k_gemm(x, ws: Sequence, n_split: int, m: Optional[int] = None):
+    """x: torch [m, in]; ws: 1..3 torch weight matrices [rows, in].  Returns fp32 torch [n_split, m, cols]."""
+    import torch
+    dtype = 1 if x.dtype == torch.bfloat16 else 0
+    m = x.shape[0] if m is None else m
+    rows = [w.shape[0] for w in ws] + [0] * (3 - len(ws))
+    ptrs = [C.c_void_p(w.data_ptr()) for w in ws] + [None] * (3 - len(ws))
+    cols = sum(rows)
+    part = torch.full((n_split, m, cols), float("nan"), dtype=torch.float32, device=x.device)
+    rc = lib.spec_k_gemm(dtype, x.data_ptr(), x.stride(0), m, x.shape[1], ptrs[0], rows[0], ptrs[1], rows[1], ptrs[2], rows[2],
+                         part.data_ptr(), cols, m, n_split, _stream_ptr())
+    if rc:
+        raise SpecError(rc, "spec_k_gemm")
+    return part
+
+
+def spec_k_attention(q, kcache, vcache, base: int, depth, anc, hq: int, hkv: int, hd: int):
+    """q: fp32 [rows, hq*hd]; caches [slots, hkv*hd] in the storage type; depth int32 [rows]; anc int32 [rows,16] or None.
+    Returns [rows, hq*hd] in the storage type."""
+    import torch
+    assert q.dtype == torch.float32
+    dtype = 1 if kcache.dtype == torch.bfloat16 else 0
+    rows = q.shape[0]
+    max_depth = int(depth.max().item())
+    max_parts = (base + max_depth) // 256 + 1
+    scratch = torch.empty(rows * hq * max_parts * (hd + 2), dtype=torch.float32, device=q.device)
+    out = torch.empty(q.shape, dtype=kcache.dtype, device=q.device)
+    rc = lib.spec_k_attention(dtype, q.data_ptr(), kcache.data_ptr(), vcache.data_ptr(), rows, hq, hkv, hd, base,
+                              depth.data_ptr(), None if anc is None else anc.data_ptr(), max_depth, scratch.data_ptr(),
+                              max_parts, out.data_ptr(), _stream_ptr())
+    if rc:
+        raise SpecError(rc, "spec_k_attention")
+    return out
+
+
+def spec_k_topk_logprob(logits, k: int):
+    import torch
+    rows, vocab = logits.shape
+    ns = (vocab + 4095) // 4096
+    sf = torch.empty(16 * ns * 18, dtype=torch.float32, device=logits.device)
+    si = torch.empty(16 * ns * 16, dtype=torch.int32, device=logits.device)
+    tok = torch.zeros((rows, 16), dtype=torch.int32, device=logits.device)
+    lp = torch.zeros((rows, 16), dtype=torch.float32, device=logits.device)
+    rc = lib.spec_k_topk_logprob(logits.data_ptr(), rows, vocab, k, sf.data_ptr(), si.data_ptr(), tok.data_ptr(), lp.data_ptr(),
+                                 _stream_ptr())
+    if rc:
+        raise SpecError(rc, "spec_k_topk_logprob")
+    return tok[:, :k], lp[:, :k]
+
+
+def upload_weights(host: Dict[str, np.ndarray], dtype: str, device: str = "cuda") -> Dict[str, "object"]:
+    """numpy float32 weights -> torch tensors on the device in the storage type (plumbing only)."""
+    import torch
+    tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    return {k: torch.from_numpy(np.ascontiguousarray(v)).to(device=device, dtype=tdt).contiguous() for k, v in host.items()}
+
+
+class Engine:
+    """Owns the torch-allocated workspace and the weight pointer table of one libspec context."""
+
+    def __init__(self, shape, weights: Dict[str, "object"], *, max_seq: Optional[int] = None, temperature: Optional[float] = None,
+                 seed: int = 0, tree=None, device: int = 0):
+        import torch
+        self.shape = shape
+        self.weights = weights                         # keeps the tensors alive: the library borrows them
+        depth, topk, total = tree if tree is not None else (shape.tree_depth, shape.tree_topk, shape.tree_total)
+        self.total = total
+        if max_seq is None:
+            max_seq = shape.prompt_len + shape.gen_tokens + total + SPEC_MAX_DEPTH + 2
+        cfg = spec_config(shape.n_layers, shape.d_model, shape.n_q_heads, shape.n_kv_heads, shape.head_dim, shape.d_ffn, shape.vocab,
+                          shape.rope_theta, shape.rms_eps, 1 if shape.dtype == "bf16" else 0, max_seq, depth, topk, total,
+                          shape.temperature if temperature is None else temperature, seed, device,
+                          torch.cuda.current_stream(device).cuda_stream, None, 0)
+        nbytes = spec_workspace_bytes(cfg)
+        if nbytes == 0:
+            raise SpecError(SPEC_EINVAL, "invalid configuration")
+        self.workspace = torch.zeros(nbytes, dtype=torch.uint8, device=f"cuda:{device}")
+        cfg.workspace = self.workspace.data_ptr()
+        cfg.workspace_bytes = nbytes
+        self.cfg = cfg
+
+        def ptr(name):
+            return C.c_void_p(weights[name].data_ptr())
+        self._layers = (spec_layer_weights * shape.n_layers)()
+        for l in range(shape.n_layers):
+            for f in LAYER_FIELDS:
+                setattr(self._layers[l], f, weights[f"layers.{l}.{f}"].data_ptr())
+        w = spec_weights()
+        w.embed, w.lm_head, w.final_norm, w.draft_fc = ptr("embed"), ptr("lm_head"), ptr("final_norm"), ptr("draft.fc")
+        w.layers = C.cast(self._layers, C.POINTER(spec_layer_weights))
+        for f in LAYER_FIELDS:
+            setattr(w.draft_layer, f, weights[f"draft.{f}"].data_ptr())
+        self._w = w
+        self.ctx = spec_create(cfg, w)
+        self.tree = Tree.empty(max(total, 1))
+
+    def close(self):
+        if getattr(self, "ctx", None):
+            spec_destroy(self.ctx)
+            self.ctx = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    # one-to-one with the C ABI
+    def prefill(self, prompt) -> int:
+        return spec_prefill(self.ctx, prompt)
+
+    def draft_tree(self) -> Tree:
+        return spec_draft_tree(self.ctx, self.tree)
+
+    def verify(self, tree: Optional[Tree] = None) -> None:
+        spec_verify(self.ctx, self.tree if tree is None else tree)
+
+    def accept(self, tree: Optional[Tree] = None) -> List[int]:
+        return spec_accept(self.ctx, self.tree if tree is None else tree)
+
+    def logits(self, n_nodes: Optional[int] = None) -> np.ndarray:
+        return spec_get_logits(self.ctx, self.tree.n_nodes if n_nodes is None else n_nodes, self.shape.vocab)
+
+    def features(self, n_nodes: Optional[int] = None) -> np.ndarray:
+        return spec_get_features(self.ctx, self.tree.n_nodes if n_nodes is None else n_nodes, self.shape.d_model)
+
+    def kv(self, which: int, layer: int, n_rows: int):
+        return spec_get_kv(self.ctx, which, layer, n_rows, self.shape.n_kv_heads * self.shape.head_dim)
+
+    @property
+    def committed(self) -> int:
+        return spec_committed(self.ctx)
+
+    def generate(self, prompt, gen: int, tree_hook=None, record: Optional[list] = None):
+        """prefill + cycles until `gen` tokens; returns (tokens[:gen], emitted-per-cycle)."""
+        out = [self.prefill(prompt)]
+        taus = []
+        while len(out) < gen:
+            t = self.draft_tree()
+            if tree_hook is not None:
+                t = tree_hook(self, t)
+            self.verify(t)
+            if record is not None:
+                record.append(dict(n=self.committed, tree=dataclasses.replace(
+                    t, token=t.token[:t.n_nodes].copy(), parent=t.parent[:t.n_nodes].copy(), depth=t.depth[:t.n_nodes].copy(),
+                    score=t.score[:t.n_nodes].copy()), logits=self.logits(t.n_nodes), feats=self.features(t.n_nodes)))
+            emitted = self.accept(t)
+            if record is not None:
+                record[-1]["emitted"] = list(emitted)
+            out += emitted
+            taus.append(len(emitted))
+        return out[:gen], taus

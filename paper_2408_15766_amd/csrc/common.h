@@ -1,0 +1,94 @@
+// Shared device helpers for the gfx950 kernels: storage types, conversions,
+// wavefront (64-lane) reductions.  Nothing here is shared with the CPU oracle.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace spec {
+
+constexpr int kWave = 64;
+
+// bfloat16 kept as raw bits; arithmetic is always done in fp32.
+struct bf16_t { uint16_t v; };
+
+__device__ __forceinline__ float bf16_bits_to_f32(uint32_t b) { return __uint_as_float(b << 16); }
+__device__ __forceinline__ uint16_t f32_to_bf16_bits(float f) {   // round to nearest, ties to even
+  uint32_t u = __float_as_uint(f);
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+__device__ __forceinline__ float to_f32(float x) { return x; }
+__device__ __forceinline__ float to_f32(bf16_t x) { return bf16_bits_to_f32(x.v); }
+template <typename T> __device__ __forceinline__ T from_f32(float x);
+template <> __device__ __forceinline__ float from_f32<float>(float x) { return x; }
+template <> __device__ __forceinline__ bf16_t from_f32<bf16_t>(float x) { bf16_t r; r.v = f32_to_bf16_bits(x); return r; }
+
+// Butterfly reductions over the 64 lanes of a wavefront; every lane gets the result.
+// The exchange pattern is fixed, so the result does not depend on the data.
+__device__ __forceinline__ float wave_sum(float x) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) x += __shfl_xor(x, o, 64);
+  return x;
+}
+__device__ __forceinline__ float wave_max(float x) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) x = fmaxf(x, __shfl_xor(x, o, 64));
+  return x;
+}
+__device__ __forceinline__ int wave_min_i(int x) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) x = min(x, __shfl_xor(x, o, 64));
+  return x;
+}
+__device__ __forceinline__ int wave_sum_i(int x) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) x += __shfl_xor(x, o, 64);
+  return x;
+}
+
+// (value, index) pair ordered by larger value first, then lower index.
+struct ValIdx { float v; int i; };
+__device__ __forceinline__ bool better(float v, int i, float v2, int i2) { return v > v2 || (v == v2 && i < i2); }
+__device__ __forceinline__ ValIdx wave_best(ValIdx a) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    float ov = __shfl_xor(a.v, o, 64);
+    int oi = __shfl_xor(a.i, o, 64);
+    if (better(ov, oi, a.v, a.i)) { a.v = ov; a.i = oi; }
+  }
+  return a;
+}
+
+// Block-wide sum for blocks of up to 16 waves; `sh` needs 16 floats.  Fixed order.
+__device__ __forceinline__ float block_sum(float x, float *sh) {
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, nw = (blockDim.x + 63) >> 6;
+  x = wave_sum(x);
+  __syncthreads();
+  if (lane == 0) sh[w] = x;
+  __syncthreads();
+  float t = 0.f;
+  for (int i = 0; i < nw; i++) t += sh[i];
+  return t;
+}
+__device__ __forceinline__ float block_max(float x, float *sh) {
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, nw = (blockDim.x + 63) >> 6;
+  x = wave_max(x);
+  __syncthreads();
+  if (lane == 0) sh[w] = x;
+  __syncthreads();
+  float t = sh[0];
+  for (int i = 1; i < nw; i++) t = fmaxf(t, sh[i]);
+  return t;
+}
+__device__ __forceinline__ ValIdx block_best(ValIdx a, float *shv, int *shi) {
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, nw = (blockDim.x + 63) >> 6;
+  a = wave_best(a);
+  __syncthreads();
+  if (lane == 0) { shv[w] = a.v; shi[w] = a.i; }
+  __syncthreads();
+  ValIdx t{shv[0], shi[0]};
+  for (int i = 1; i < nw; i++) if (better(shv[i], shi[i], t.v, t.i)) { t.v = shv[i]; t.i = shi[i]; }
+  return t;
+}
+
+}  // namespace spec

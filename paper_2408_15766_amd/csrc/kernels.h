@@ -1,0 +1,127 @@
+// Host-callable launchers of the gfx950 kernels.  All pointers are device
+// pointers unless a comment says otherwise; dtype 0 = fp32, 1 = bf16 storage.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace spec {
+
+constexpr int kMaxDepth = 15;          // longest root-to-node path handled by the tail of the attention
+constexpr int kAncStride = kMaxDepth + 1;
+constexpr int kMaxTopK = 16;
+constexpr int kMaxNodes = 128;
+constexpr int kAttnPart = 256;         // key positions per attention partial (fixed absolute boundaries)
+constexpr int kTopkSlice = 4096;       // vocabulary entries per first-stage top-k workgroup
+
+// ---- gemm.hip --------------------------------------------------------------------------------
+struct GemmArgs {
+  const void *x;  int ldx;  int m;      // X [m, in], row stride ldx elements, 1 <= m <= 128
+  int in;                               // K, a multiple of 16 bytes / element size
+  const void *seg_w[3];                 // up to three weight matrices [rows, in] sharing X (e.g. q, k, v)
+  int seg_rows[3];
+  int seg_blocks[3];                    // ceil(rows / 32)
+  int seg_col0[3];                      // first output column of the segment
+  int nseg, total_blocks;
+  float *part;  int ldp;  int m_pad;    // partial sums [n_split][m_pad][ldp], fp32
+  int n_split;                          // K is cut into n_split ranges of whole slabs, balanced to one slab
+};
+hipError_t launch_gemm(int dtype, const GemmArgs &a, hipStream_t st);
+int gemm_k_per_slab(int dtype);
+int gemm_k_per_iter(int dtype);
+int gemm_rows_per_group();
+
+// ---- rowops.hip ------------------------------------------------------------------------------
+// cos/sin of pos[i] * theta^(-2j/hd) for j < hd/2, angles formed in double precision.
+hipError_t launch_rope_table(const int *pos, int rows, int head_dim, float theta, float2 *table, hipStream_t st);
+// h[i] = embed[token[i]] (fp32);  x[i] = rmsnorm(h[i]) * w  in the storage type.
+hipError_t launch_embed_norm(int dtype, const void *embed, const int *token, int rows, int d, const void *norm_w,
+                             float eps, float *h, void *x, hipStream_t st);
+// xcat[i] = [feat[src_row[i]] ; embed[token[i]]]  ([rows, 2d], storage type).  src_row == nullptr: identity.
+hipError_t launch_concat_feat_embed(int dtype, const void *feat, const int *src_row, const void *embed,
+                                    const int *token, int rows, int d, void *xcat, hipStream_t st);
+// h[i] = (residual ? h[i] : 0) + sum_s part[s][i][:d];  x[i] = norm_w ? rmsnorm(h[i]) * norm_w : h[i].
+hipError_t launch_reduce_add_norm(int dtype, const float *part, int n_split, int m_pad, int ldp, int rows, int d,
+                                  int residual, const void *norm_w, float eps, float *h, void *x, hipStream_t st);
+// Sums the QKV partials, rotates q and k by the row's position, writes q [rows, hq*hd] (always fp32) and
+// the row's key/value (storage type) into cache slot slot[i].  Cache layout [max_seq][hkv*hd].
+hipError_t launch_reduce_rope_kv(int dtype, const float *part, int n_split, int m_pad, int ldp, int rows, int hq, int hkv,
+                                 int hd, const float2 *rope, const int *slot, void *q, void *kcache, void *vcache,
+                                 hipStream_t st);
+// act[i][c] = silu(g) * u with g = sum_s part[s][i][c], u = sum_s part[s][i][f + c].
+hipError_t launch_reduce_swiglu(int dtype, const float *part, int n_split, int m_pad, int ldp, int rows, int f, void *act,
+                                hipStream_t st);
+
+// Row i of a causal chain starting at cache slot `base`: slot = base + i, position = slot + pos_offset,
+// depth = i (its tail is the chain itself).
+hipError_t launch_chain_rows(int base, int rows, int pos_offset, int *pos, int *slot, int *depth, hipStream_t st);
+
+// ---- attention.hip ---------------------------------------------------------------------------
+// Row i sits at key position base + depth[i] and attends to positions 0 .. base + depth[i]:
+// position q < base lives in cache slot q; position q >= base lives in slot base + anc[i][q - base]
+// (anc == nullptr: slot q, i.e. a causal chain).  Output [rows, hq*hd] in the storage type.
+struct AttnArgs {
+  const void *q;                        // fp32 [rows, hq*hd]
+  const void *kcache; const void *vcache;
+  int rows, hq, hkv, hd, base;
+  const int *depth;                     // [rows]
+  const int *anc;                       // [rows][kAncStride] or nullptr
+  float scale;
+  float *part;                          // scratch: [rows][hq][max_parts][hd + 2]
+  int max_parts;
+  void *out;
+};
+hipError_t launch_attention(int dtype, const AttnArgs &a, int max_pos, hipStream_t st);
+
+// ---- select.hip ------------------------------------------------------------------------------
+// argmax over each row of logits [rows, vocab] (ld = vocab), lower index on ties.
+hipError_t launch_rows_argmax(const float *logits, int rows, int vocab, int *out, hipStream_t st);
+// per row, with x = logit / temp: stats[row] = {max x, sum exp(x - max x)}
+hipError_t launch_rows_softmax_stats(const float *logits, int rows, int vocab, float temp, float2 *stats, hipStream_t st);
+// per row: top-k (token, log-softmax) pairs, best first, lower token on ties.  Two stages through scratch.
+hipError_t launch_rows_topk_logprob(const float *logits, int rows, int vocab, int k, float *sc_val, int *sc_idx,
+                                    float2 *sc_stat, int *top_tok, float *top_lp, hipStream_t st);
+
+// Device-resident state of the draft tree expansion.
+struct DraftState {
+  int *pool_tok, *pool_par, *pool_dep; float *pool_sc;   // candidate pool
+  int *n_pool;                                           // [1]
+  int *front_pool;                                       // [K] pool index of each frontier row
+  int *front_tok;                                        // [K] token of each frontier row
+  int *front_src;                                        // [K] row of the previous step's output holding the parent feature
+  int *front_depth;                                      // [K] depth argument for the attention (tail length - 1)
+  int *front_anc;                                        // [K][kAncStride] scratch-slot offsets of the ancestors and itself
+  int *front_slot;                                       // [K] cache slot the row's key/value go to
+  int *front_pos;                                        // [K] rotary position
+};
+// After the root step: pool <- top-k of the root row; frontier <- those k nodes.
+hipError_t launch_pool_init(const DraftState &s, const int *top_tok, const float *top_lp, int k, int root_row,
+                            int n_draft, hipStream_t st);
+// After expansion step t (frontier rows = k nodes of depth t-1): append k*k children; if `select_next`,
+// choose the k best children as the next frontier and derive its attention tables.
+hipError_t launch_pool_expand(const DraftState &s, const int *top_tok, const float *top_lp, int k, int step,
+                              int n_draft, int select_next, hipStream_t st);
+// Rerank: best (total-1) pool entries by score (ties: lower pool index), kept in pool order.
+// tree_* arrays have room for `total` nodes; node 0 = root.
+hipError_t launch_rerank(const DraftState &s, int total, const int *root_tok, int *tree_n, int *tree_tok, int *tree_par,
+                         int *tree_dep, float *tree_sc, hipStream_t st);
+
+struct AcceptResult {                   // lives on the device; copied to the host after acceptance
+  int n_acc;                            // m: accepted draft nodes
+  int node[kMaxDepth + 1];              // node[0] = 0 (root), node[d] = accepted node of depth d
+  int token[kMaxDepth + 1];             // m accepted tokens then the bonus token
+};
+hipError_t launch_accept_greedy(const int *row_argmax, const int *tree_tok, const int *tree_par, int n_nodes,
+                                AcceptResult *res, hipStream_t st);
+hipError_t launch_accept_sample(const float *logits, int vocab, const float2 *stats, float temp, const int *tree_tok,
+                                const int *tree_par, int n_nodes, uint64_t seed, uint32_t cycle, AcceptResult *res,
+                                hipStream_t st);
+// Sample one token from softmax(logits / temp) by Gumbel-max with stream (seed, cycle, node).
+hipError_t launch_sample_row(const float *logits, int vocab, float temp, uint64_t seed, uint32_t cycle, uint32_t node,
+                             int *out, hipStream_t st);
+// Commit: in every layer move key/value of accepted node d from slot n + node[d] to slot n + d; gather
+// the features of root + accepted rows and the tokens for the next draft root step; *root_tok <- bonus.
+hipError_t launch_commit(int dtype, const AcceptResult *res, void *kv_base, size_t layer_stride, size_t kv_stride,
+                         int n_layers, int row_elems, int n, const void *feat, int d, void *pend_feat, int *pend_tok,
+                         int *root_tok, hipStream_t st);
+
+}  // namespace spec

@@ -1,0 +1,448 @@
+// Selection kernels of the speculative-decoding cycle: vocabulary reductions (argmax,
+// softmax statistics, top-k log-probabilities), the draft tree's candidate pool (expansion,
+// frontier choice, rerank), acceptance (greedy walk, multi-round rejection sampling with a
+// counter-based RNG) and the KV-cache compaction that commits the accepted path.
+//
+// Ordering rule everywhere: larger value first, equal values by lower index, so results are
+// unique and independent of how the work is split over lanes.
+#include <limits.h>
+
+#include "common.h"
+#include "kernels.h"
+
+namespace spec {
+
+constexpr int kSelThreads = 256;
+
+// ---- counter-based RNG: splitmix64 finaliser chained over (seed, cycle, node, draw) --------
+__device__ __forceinline__ uint64_t mix64(uint64_t x) {
+  x ^= x >> 30; x *= 0xBF58476D1CE4E5B9ull;
+  x ^= x >> 27; x *= 0x94D049BB133111EBull;
+  x ^= x >> 31;
+  return x;
+}
+__device__ __forceinline__ uint64_t rng_stream(uint64_t seed, uint32_t cycle, uint32_t node) {
+  uint64_t s = mix64(seed + 0x9E3779B97F4A7C15ull);
+  s = mix64(s + cycle);
+  return mix64(s + node);
+}
+// 23 random bits centred in their cell: never 0 or 1, exact in fp32.
+__device__ __forceinline__ float rng_uniform(uint64_t stream, uint64_t draw) {
+  return ((float)(mix64(stream + draw) >> 41) + 0.5f) * 1.1920928955078125e-07f;
+}
+__device__ __forceinline__ float rng_gumbel(uint64_t stream, int v) {
+  return -logf(-logf(rng_uniform(stream, (1ull << 32) + (uint64_t)v)));
+}
+
+// ---- per-row argmax ------------------------------------------------------------------------
+__global__ __launch_bounds__(kSelThreads) void rows_argmax_kernel(const float *logits, int vocab, int *out) {
+  __shared__ float shv[16];
+  __shared__ int shi[16];
+  const float *row = logits + (size_t)blockIdx.x * vocab;
+  ValIdx b{-INFINITY, INT_MAX};
+  for (int c = threadIdx.x; c < vocab; c += kSelThreads) {
+    const float x = row[c];
+    if (x > b.v || b.i == INT_MAX) { b.v = x; b.i = c; }     // ascending c: strict > keeps the lower index
+  }
+  b = block_best(b, shv, shi);
+  if (threadIdx.x == 0) out[blockIdx.x] = b.i;
+}
+hipError_t launch_rows_argmax(const float *logits, int rows, int vocab, int *out, hipStream_t st) {
+  if (rows < 1 || vocab < 1) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(rows_argmax_kernel, dim3(rows), dim3(kSelThreads), 0, st, logits, vocab, out);
+  return hipGetLastError();
+}
+
+// ---- per-row softmax statistics at temperature T: max(x) and sum exp(x - max), x = logit / T
+__global__ __launch_bounds__(kSelThreads) void rows_softmax_stats_kernel(const float *logits, int vocab, float temp,
+                                                                         float2 *stats) {
+  __shared__ float sh[16];
+  const float *row = logits + (size_t)blockIdx.x * vocab;
+  float m = -INFINITY;
+  for (int c = threadIdx.x; c < vocab; c += kSelThreads) m = fmaxf(m, row[c] / temp);
+  m = block_max(m, sh);
+  float s = 0.f;
+  for (int c = threadIdx.x; c < vocab; c += kSelThreads) s += expf(row[c] / temp - m);
+  s = block_sum(s, sh);
+  if (threadIdx.x == 0) stats[blockIdx.x] = make_float2(m, s);
+}
+hipError_t launch_rows_softmax_stats(const float *logits, int rows, int vocab, float temp, float2 *stats, hipStream_t st) {
+  if (rows < 1 || vocab < 1 || !(temp > 0.f)) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(rows_softmax_stats_kernel, dim3(rows), dim3(kSelThreads), 0, st, logits, vocab, temp, stats);
+  return hipGetLastError();
+}
+
+// ---- per-row top-k log-probabilities -------------------------------------------------------
+// Stage 1: one workgroup per (slice of kTopkSlice entries, row): slice max, slice sum-exp and the
+// slice's k best entries, found by k rounds of block-wide argmax over register-resident values.
+__global__ __launch_bounds__(kSelThreads) void topk_slice_kernel(const float *logits, int vocab, int k, int n_slices,
+                                                                 float *sc_val, int *sc_idx, float2 *sc_stat) {
+  constexpr int PER = kTopkSlice / kSelThreads;   // 16
+  __shared__ float shv[16];
+  __shared__ int shi[16];
+  const int slice = blockIdx.x, rowi = blockIdx.y, t = threadIdx.x;
+  const int c0 = slice * kTopkSlice;
+  const float *row = logits + (size_t)rowi * vocab;
+  float v[PER];
+#pragma unroll
+  for (int e = 0; e < PER; e++) {
+    const int c = c0 + t + e * kSelThreads;
+    v[e] = c < vocab ? row[c] : -INFINITY;
+  }
+  float m = v[0];
+#pragma unroll
+  for (int e = 1; e < PER; e++) m = fmaxf(m, v[e]);
+  m = block_max(m, shv);
+  float s = 0.f;
+#pragma unroll
+  for (int e = 0; e < PER; e++) s += expf(v[e] - m);        // exp(-inf) = 0 for padding
+  s = block_sum(s, shv);
+  const size_t o = ((size_t)rowi * n_slices + slice);
+  if (t == 0) sc_stat[o] = make_float2(m, s);
+  uint32_t taken = 0;
+  for (int r = 0; r < k; r++) {
+    ValIdx b{-INFINITY, INT_MAX};
+#pragma unroll
+    for (int e = 0; e < PER; e++) {
+      const int c = c0 + t + e * kSelThreads;
+      if (!((taken >> e) & 1u) && c < vocab && (v[e] > b.v || b.i == INT_MAX)) { b.v = v[e]; b.i = c; }
+    }
+    b = block_best(b, shv, shi);
+    if (t == 0) { sc_val[o * kMaxTopK + r] = b.v; sc_idx[o * kMaxTopK + r] = b.i; }
+    if (b.i != INT_MAX && (b.i - c0) % kSelThreads == t) taken |= 1u << ((b.i - c0) / kSelThreads);
+  }
+}
+// Stage 2: one wavefront per row merges the slices: log-sum-exp and the k best of all candidates.
+__global__ __launch_bounds__(64) void topk_merge_kernel(int k, int n_slices, const float *sc_val, const int *sc_idx,
+                                                        const float2 *sc_stat, int *top_tok, float *top_lp) {
+  const int rowi = blockIdx.x, lane = threadIdx.x;
+  const float2 *stat = sc_stat + (size_t)rowi * n_slices;
+  float m = -INFINITY;
+  for (int s = lane; s < n_slices; s += 64) m = fmaxf(m, stat[s].x);
+  m = wave_max(m);
+  float tot = 0.f;
+  for (int s0 = 0; s0 < n_slices; s0 += 64) {            // slices in ascending groups of 64, fixed butterfly inside
+    const int s = s0 + lane;
+    tot += wave_sum(s < n_slices ? stat[s].y * expf(stat[s].x - m) : 0.f);
+  }
+  const float lse = m + logf(tot);
+  const int n_cand = n_slices * k;                          // candidate id = slice * k + r
+  const float *val = sc_val + (size_t)rowi * n_slices * kMaxTopK;
+  const int *idx = sc_idx + (size_t)rowi * n_slices * kMaxTopK;
+  // a lane's candidates: ids lane, lane + 64, ...; taken ones are marked in a bitmask (<= 64 per lane)
+  uint64_t taken = 0;
+  for (int r = 0; r < k; r++) {
+    ValIdx b{-INFINITY, INT_MAX};
+    int e = 0;
+    for (int id = lane; id < n_cand; id += 64, e++) {
+      if ((taken >> e) & 1ull) continue;
+      const int sl = id / k, rr = id % k;
+      const float x = val[sl * kMaxTopK + rr];
+      const int c = idx[sl * kMaxTopK + rr];
+      if (c != INT_MAX && better(x, c, b.v, b.i)) { b.v = x; b.i = c; }
+    }
+    b = wave_best(b);
+    e = 0;
+    for (int id = lane; id < n_cand; id += 64, e++) {
+      const int sl = id / k, rr = id % k;
+      if (idx[sl * kMaxTopK + rr] == b.i && b.i != INT_MAX) taken |= 1ull << e;
+    }
+    if (lane == 0) { top_tok[rowi * kMaxTopK + r] = b.i; top_lp[rowi * kMaxTopK + r] = b.v - lse; }
+  }
+}
+hipError_t launch_rows_topk_logprob(const float *logits, int rows, int vocab, int k, float *sc_val, int *sc_idx,
+                                    float2 *sc_stat, int *top_tok, float *top_lp, hipStream_t st) {
+  const int n_slices = (vocab + kTopkSlice - 1) / kTopkSlice;
+  if (rows < 1 || k < 1 || k > kMaxTopK || k > vocab || n_slices * k > 64 * 64) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(topk_slice_kernel, dim3(n_slices, rows), dim3(kSelThreads), 0, st, logits, vocab, k, n_slices, sc_val,
+                     sc_idx, sc_stat);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(topk_merge_kernel, dim3(rows), dim3(64), 0, st, k, n_slices, sc_val, sc_idx, sc_stat, top_tok, top_lp);
+  return hipGetLastError();
+}
+
+// ---- candidate pool ------------------------------------------------------------------------
+// top_tok / top_lp rows have stride kMaxTopK.
+__global__ void pool_init_kernel(DraftState s, const int *top_tok, const float *top_lp, int k, int root_row, int n_draft) {
+  const int r = threadIdx.x;
+  if (r < k) {
+    s.pool_tok[r] = top_tok[r]; s.pool_par[r] = -1; s.pool_dep[r] = 1; s.pool_sc[r] = top_lp[r];
+    s.front_pool[r] = r; s.front_tok[r] = top_tok[r]; s.front_src[r] = root_row; s.front_depth[r] = 0;
+    s.front_anc[r * kAncStride] = r;
+    s.front_slot[r] = n_draft + r;
+    s.front_pos[r] = n_draft + 1;
+  }
+  if (r == 0) *s.n_pool = k;
+}
+hipError_t launch_pool_init(const DraftState &s, const int *top_tok, const float *top_lp, int k, int root_row,
+                            int n_draft, hipStream_t st) {
+  if (k < 1 || k > kMaxTopK) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(pool_init_kernel, dim3(1), dim3(64), 0, st, s, top_tok, top_lp, k, root_row, n_draft);
+  return hipGetLastError();
+}
+
+// `step` t in 2..D: the k frontier rows are nodes of depth t-1; their children have depth t.
+__global__ __launch_bounds__(kSelThreads) void pool_expand_kernel(DraftState s, const int *top_tok, const float *top_lp,
+                                                                  int k, int step, int n_draft, int select_next) {
+  __shared__ float sc[kMaxTopK * kMaxTopK];
+  __shared__ int old_anc[kMaxTopK * kAncStride];
+  __shared__ int old_pool[kMaxTopK];
+  const int t = threadIdx.x, kk = k * k;
+  const int base = *s.n_pool;
+  if (t < k) old_pool[t] = s.front_pool[t];
+  for (int e = t; e < k * kAncStride; e += kSelThreads) old_anc[e] = s.front_anc[e];
+  __syncthreads();
+  int r = 0, j = 0, tok = 0;
+  if (t < kk) {
+    r = t / k; j = t % k;                                   // children in (frontier order, best first) order
+    tok = top_tok[r * kMaxTopK + j];
+    const float v = s.pool_sc[old_pool[r]] + top_lp[r * kMaxTopK + j];
+    sc[t] = v;
+    s.pool_tok[base + t] = tok; s.pool_par[base + t] = old_pool[r]; s.pool_dep[base + t] = step; s.pool_sc[base + t] = v;
+  }
+  __syncthreads();
+  if (t == 0) *s.n_pool = base + kk;
+  if (!select_next || t >= kk) return;
+  int rank = 0;
+  for (int c = 0; c < kk; c++) rank += better(sc[c], c, sc[t], t) ? 1 : 0;
+  if (rank >= k) return;
+  // this child is row `rank` of the next expansion step (step + 1): depth argument step - 1
+  s.front_pool[rank] = base + t; s.front_tok[rank] = tok; s.front_src[rank] = r; s.front_depth[rank] = step - 1;
+  for (int a = 0; a < step - 1; a++) s.front_anc[rank * kAncStride + a] = old_anc[r * kAncStride + a];
+  s.front_anc[rank * kAncStride + step - 1] = (step - 1) * k + rank;
+  s.front_slot[rank] = n_draft + (step - 1) * k + rank;
+  s.front_pos[rank] = n_draft + 1 + (step - 1);
+}
+hipError_t launch_pool_expand(const DraftState &s, const int *top_tok, const float *top_lp, int k, int step,
+                              int n_draft, int select_next, hipStream_t st) {
+  if (k < 1 || k > kMaxTopK || step < 2 || step > kMaxDepth) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(pool_expand_kernel, dim3(1), dim3(kSelThreads), 0, st, s, top_tok, top_lp, k, step, n_draft, select_next);
+  return hipGetLastError();
+}
+
+// ---- rerank --------------------------------------------------------------------------------
+constexpr int kMaxPool = kMaxTopK + (kMaxDepth - 1) * kMaxTopK * kMaxTopK;    // 3600
+__global__ __launch_bounds__(kSelThreads) void rerank_kernel(DraftState s, int total, const int *root_tok, int *tree_n,
+                                                             int *tree_tok, int *tree_par, int *tree_dep, float *tree_sc) {
+  __shared__ float sc[kMaxPool];
+  __shared__ short node_of[kMaxPool];                       // 0 = not kept, else node index
+  const int t = threadIdx.x, n = *s.n_pool;
+  const int keep = min(total - 1, n);
+  for (int c = t; c < n; c += kSelThreads) sc[c] = s.pool_sc[c];
+  __syncthreads();
+  for (int c = t; c < n; c += kSelThreads) {
+    int rank = 0;
+    const float v = sc[c];
+    for (int o = 0; o < n; o++) rank += better(sc[o], o, v, c) ? 1 : 0;
+    node_of[c] = rank < keep ? 1 : 0;
+  }
+  __syncthreads();
+  // node index = 1 + number of kept entries with a lower pool index (kept in pool order: parents first)
+  int my_nodes[(kMaxPool + kSelThreads - 1) / kSelThreads];
+  int e = 0;
+  for (int c = t; c < n; c += kSelThreads, e++) {
+    int cnt = 0;
+    if (node_of[c]) for (int o = 0; o < c; o++) cnt += node_of[o] ? 1 : 0;
+    my_nodes[e] = node_of[c] ? cnt + 1 : 0;
+  }
+  __syncthreads();
+  e = 0;
+  for (int c = t; c < n; c += kSelThreads, e++) node_of[c] = (short)my_nodes[e];
+  __syncthreads();
+  for (int c = t; c < n; c += kSelThreads) {
+    const int j = node_of[c];
+    if (!j) continue;
+    const int par = s.pool_par[c];
+    tree_tok[j] = s.pool_tok[c];
+    tree_par[j] = par < 0 ? 0 : node_of[par];
+    tree_dep[j] = s.pool_dep[c];
+    tree_sc[j] = sc[c];
+  }
+  if (t == 0) { tree_tok[0] = *root_tok; tree_par[0] = -1; tree_dep[0] = 0; tree_sc[0] = 0.f; *tree_n = keep + 1; }
+}
+hipError_t launch_rerank(const DraftState &s, int total, const int *root_tok, int *tree_n, int *tree_tok, int *tree_par,
+                         int *tree_dep, float *tree_sc, hipStream_t st) {
+  if (total < 1 || total > kMaxNodes) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(rerank_kernel, dim3(1), dim3(kSelThreads), 0, st, s, total, root_tok, tree_n, tree_tok, tree_par, tree_dep,
+                     tree_sc);
+  return hipGetLastError();
+}
+
+// ---- acceptance ----------------------------------------------------------------------------
+// First child of `cur` (lowest node index) carrying `tok`, or INT_MAX.  One wavefront.
+__device__ __forceinline__ int find_child(const int *tree_tok, const int *tree_par, int n_nodes, int cur, int tok, int lane) {
+  int best = INT_MAX;
+  for (int c = lane; c < n_nodes; c += 64)
+    if (c > cur && tree_par[c] == cur && tree_tok[c] == tok) best = min(best, c);
+  return wave_min_i(best);
+}
+
+__global__ __launch_bounds__(64) void accept_greedy_kernel(const int *row_argmax, const int *tree_tok, const int *tree_par,
+                                                           int n_nodes, AcceptResult *res) {
+  const int lane = threadIdx.x;
+  int cur = 0, m = 0;
+  if (lane == 0) res->node[0] = 0;
+  for (int step = 0; step <= kMaxDepth; step++) {
+    const int best = row_argmax[cur];
+    const int c = m < kMaxDepth ? find_child(tree_tok, tree_par, n_nodes, cur, best, lane) : INT_MAX;
+    if (lane == 0) res->token[m] = best;                    // accepted token, or the bonus when the walk stops
+    if (c == INT_MAX) break;
+    cur = c; m++;
+    if (lane == 0) res->node[m] = cur;
+  }
+  if (lane == 0) res->n_acc = m;
+}
+hipError_t launch_accept_greedy(const int *row_argmax, const int *tree_tok, const int *tree_par, int n_nodes,
+                                AcceptResult *res, hipStream_t st) {
+  if (n_nodes < 1 || n_nodes > kMaxNodes) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(accept_greedy_kernel, dim3(1), dim3(64), 0, st, row_argmax, tree_tok, tree_par, n_nodes, res);
+  return hipGetLastError();
+}
+
+// Gumbel-max over one row, skipping `n_rem` removed tokens.  Whole block; result to every thread.
+__device__ __forceinline__ int gumbel_argmax(const float *row, int vocab, float temp, uint64_t stream, const int *rem,
+                                             int n_rem, float *shv, int *shi) {
+  ValIdx b{-INFINITY, INT_MAX};
+  for (int v = threadIdx.x; v < vocab; v += blockDim.x) {
+    bool skip = false;
+    for (int r = 0; r < n_rem; r++) skip |= rem[r] == v;
+    if (skip) continue;
+    const float z = row[v] / temp + rng_gumbel(stream, v);
+    if (z > b.v || b.i == INT_MAX) { b.v = z; b.i = v; }
+  }
+  return block_best(b, shv, shi).i;
+}
+
+// Multi-round rejection sampling down the tree.  The children of a node were chosen
+// deterministically by the draft (top-k), so each is a point-mass proposal: child c is accepted
+// with probability p'(c), where p' is the target distribution with the already rejected siblings
+// removed and renormalised; when all children are rejected the bonus token is drawn from p'.
+__global__ __launch_bounds__(kSelThreads) void accept_sample_kernel(const float *logits, int vocab, const float2 *stats,
+                                                                    float temp, const int *tree_tok, const int *tree_par,
+                                                                    int n_nodes, uint64_t seed, uint32_t cycle,
+                                                                    AcceptResult *res) {
+  __shared__ float shv[16];
+  __shared__ int shi[16];
+  __shared__ int rem[kMaxNodes];
+  __shared__ int sh_next, sh_nrem;
+  int cur = 0, m = 0;
+  if (threadIdx.x == 0) res->node[0] = 0;
+  for (int step = 0; step <= kMaxDepth; step++) {
+    const uint64_t stream = rng_stream(seed, cycle, (uint32_t)cur);
+    if (threadIdx.x == 0) {
+      const float *row = logits + (size_t)cur * vocab;
+      const float2 st = stats[cur];
+      float removed = 0.f;                                  // probability mass of the rejected siblings
+      int n_rem = 0, next = -1, ord = 0;
+      for (int c = cur + 1; c < n_nodes && next < 0 && m < kMaxDepth; c++) {
+        if (tree_par[c] != cur) continue;
+        const int tok = tree_tok[c];
+        bool dup = false;
+        for (int r = 0; r < n_rem; r++) dup |= rem[r] == tok;
+        const float p0 = dup ? 0.f : expf(row[tok] / temp - st.x) / st.y;
+        const float rest = 1.0f - removed;
+        const float u = rng_uniform(stream, (uint64_t)ord);
+        ord++;
+        if (u < p0 / rest) { next = c; break; }
+        if (!dup) { removed += p0; rem[n_rem++] = tok; }
+        if (!(1.0f - removed > 0.f)) { next = c; break; }   // nothing left in the residual: c was certain
+      }
+      sh_next = next; sh_nrem = n_rem;
+    }
+    __syncthreads();
+    const int next = sh_next, n_rem = sh_nrem;
+    if (next >= 0) {
+      if (threadIdx.x == 0) { res->token[m] = tree_tok[next]; res->node[m + 1] = next; }
+      cur = next; m++;
+      __syncthreads();
+      continue;
+    }
+    const int bonus = gumbel_argmax(logits + (size_t)cur * vocab, vocab, temp, stream, rem, n_rem, shv, shi);
+    if (threadIdx.x == 0) res->token[m] = bonus;
+    break;
+  }
+  if (threadIdx.x == 0) res->n_acc = m;
+}
+hipError_t launch_accept_sample(const float *logits, int vocab, const float2 *stats, float temp, const int *tree_tok,
+                                const int *tree_par, int n_nodes, uint64_t seed, uint32_t cycle, AcceptResult *res,
+                                hipStream_t st) {
+  if (n_nodes < 1 || n_nodes > kMaxNodes || !(temp > 0.f)) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(accept_sample_kernel, dim3(1), dim3(kSelThreads), 0, st, logits, vocab, stats, temp, tree_tok, tree_par,
+                     n_nodes, seed, cycle, res);
+  return hipGetLastError();
+}
+
+__global__ __launch_bounds__(kSelThreads) void sample_row_kernel(const float *logits, int vocab, float temp, uint64_t seed,
+                                                                 uint32_t cycle, uint32_t node, int *out) {
+  __shared__ float shv[16];
+  __shared__ int shi[16];
+  const int tok = gumbel_argmax(logits, vocab, temp, rng_stream(seed, cycle, node), nullptr, 0, shv, shi);
+  if (threadIdx.x == 0) *out = tok;
+}
+hipError_t launch_sample_row(const float *logits, int vocab, float temp, uint64_t seed, uint32_t cycle, uint32_t node,
+                             int *out, hipStream_t st) {
+  if (vocab < 1 || !(temp > 0.f)) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(sample_row_kernel, dim3(1), dim3(kSelThreads), 0, st, logits, vocab, temp, seed, cycle, node, out);
+  return hipGetLastError();
+}
+
+// ---- commit: KV compaction + hand-off ------------------------------------------------------
+// Thread = one 16-byte chunk of one (layer, key|value) row; it moves that chunk for depths 1..m in
+// ascending order.  Depth d's destination slot n+d is never a later depth's source (sources
+// n+node[d'] have node[d'] > d for d' > d), and a chunk column is owned by one thread, so the
+// in-place move is race-free.
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;
+__global__ __launch_bounds__(kSelThreads) void compact_kv_kernel(const AcceptResult *res, char *kv_base, size_t layer_bytes,
+                                                                 size_t kv_bytes, int n_layers, int row_bytes, int n) {
+  const int m = res->n_acc;
+  if (m == 0) return;
+  const int chunks = row_bytes / 16;
+  const size_t total = (size_t)n_layers * 2 * chunks;
+  for (size_t w = (size_t)blockIdx.x * kSelThreads + threadIdx.x; w < total; w += (size_t)gridDim.x * kSelThreads) {
+    const int ch = (int)(w % chunks);
+    const int kv = (int)((w / chunks) & 1);
+    const int l = (int)(w / chunks / 2);
+    char *base = kv_base + (size_t)l * layer_bytes + (size_t)kv * kv_bytes + (size_t)ch * 16;
+    for (int d = 1; d <= m; d++) {
+      const int src = n + res->node[d], dst = n + d;
+      if (src != dst) *(u32x4_t *)(base + (size_t)dst * row_bytes) = *(const u32x4_t *)(base + (size_t)src * row_bytes);
+    }
+  }
+}
+// Features of root + accepted rows and the matching tokens for the next draft root step.
+template <typename T>
+__global__ __launch_bounds__(kSelThreads) void handoff_kernel(const AcceptResult *res, const T *feat, int d, T *pend_feat,
+                                                              int *pend_tok, int *root_tok) {
+  const int r = blockIdx.x, m = res->n_acc;
+  if (r > m) return;
+  const T *src = feat + (size_t)res->node[r] * d;
+  T *dst = pend_feat + (size_t)r * d;
+  for (int c = threadIdx.x; c < d; c += kSelThreads) dst[c] = src[c];
+  if (threadIdx.x == 0) {
+    pend_tok[r] = res->token[r];
+    if (r == m) *root_tok = res->token[m];
+  }
+}
+hipError_t launch_commit(int dtype, const AcceptResult *res, void *kv_base, size_t layer_stride, size_t kv_stride,
+                         int n_layers, int row_elems, int n, const void *feat, int d, void *pend_feat, int *pend_tok,
+                         int *root_tok, hipStream_t st) {
+  const size_t esz = dtype == 1 ? 2 : 4;
+  const int row_bytes = (int)(row_elems * esz);
+  if (row_bytes % 16 != 0 || n_layers < 1) return hipErrorInvalidValue;
+  const size_t total = (size_t)n_layers * 2 * (row_bytes / 16);
+  const int blocks = (int)((total + kSelThreads - 1) / kSelThreads);
+  hipLaunchKernelGGL(compact_kv_kernel, dim3(blocks > 2048 ? 2048 : blocks), dim3(kSelThreads), 0, st, res, (char *)kv_base,
+                     layer_stride * esz, kv_stride * esz, n_layers, row_bytes, n);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  if (dtype == 1)
+    hipLaunchKernelGGL(handoff_kernel<bf16_t>, dim3(kMaxDepth + 1), dim3(kSelThreads), 0, st, res, (const bf16_t *)feat, d,
+                       (bf16_t *)pend_feat, pend_tok, root_tok);
+  else
+    hipLaunchKernelGGL(handoff_kernel<float>, dim3(kMaxDepth + 1), dim3(kSelThreads), 0, st, res, (const float *)feat, d,
+                       (float *)pend_feat, pend_tok, root_tok);
+  return hipGetLastError();
+}
+
+}  // namespace spec

@@ -1,0 +1,233 @@
+"""GPU end-to-end parity of the C-ABI decode path against the CPU oracle."""
+import dataclasses
+
+import numpy as np
+import pytest
+
+import workload as wl
+import oracle
+from oracle.llama import as_dtype
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def env():
+    import torch
+    import paper_2408_15766_amd as P
+    assert torch.cuda.is_available()
+    return torch, P
+
+
+@pytest.fixture(scope="module")
+def tiny_gpu(env):
+    torch, P = env
+    sh = wl.TINY
+    hw = wl.make_weights(sh)
+    return sh, hw, as_dtype(hw, np.float64), wl.make_prompt(sh), P.upload_weights(hw, sh.dtype)
+
+
+def oracle_tree_to_gpu(P, t, cap):
+    g = P.Tree.empty(cap)
+    n = t.n_nodes
+    g.token[:n], g.parent[:n], g.depth[:n], g.score[:n] = t.token, t.parent, t.depth, t.score
+    g.n_nodes = n
+    return g
+
+
+def test_tiny_fp32_greedy_matches_oracle_token_for_token(env, tiny_gpu):
+    """Plain decoding through the same kernels (tree of the root alone)."""
+    torch, P = env
+    sh, hw, w64, prompt, dw = tiny_gpu
+    eng = P.Engine(sh, dw, tree=(1, 1, 1))
+    got, taus = eng.generate(prompt, sh.gen_tokens)
+    want = oracle.greedy_decode(w64, sh, prompt, sh.gen_tokens)
+    assert got == want and set(taus) == {1}
+
+
+def test_tiny_fp32_spec_matches_oracle_per_cycle(env, tiny_gpu):
+    """Config 0: tokens identical, the draft tree identical, logits within 1e-4, features, KV cache."""
+    torch, P = env
+    sh, hw, w64, prompt, dw = tiny_gpu
+    eng = P.Engine(sh, dw)
+    grec, orec = [], []
+    got, gt = eng.generate(prompt, sh.gen_tokens, record=grec)
+    want, wt = oracle.spec_decode(w64, sh, prompt, sh.gen_tokens, record=orec)
+    assert got == want == oracle.greedy_decode(w64, sh, prompt, sh.gen_tokens)
+    assert gt == wt
+    assert len(grec) == len(orec)
+    for a, b in zip(grec, orec):
+        ta, tb = a["tree"], b["tree"]
+        assert ta.n_nodes == tb.n_nodes == sh.tree_total
+        assert list(ta.token) == list(tb.token) and list(ta.parent) == list(tb.parent) and list(ta.depth) == list(tb.depth)
+        assert np.abs(ta.score - tb.score).max() < 2e-5
+        assert np.abs(a["logits"] - b["logits"]).max() < 1e-4
+        assert np.abs(a["feats"] - b["feats"]).max() < 1e-4
+
+
+def forge_hook(stream, n_prompt, plan, rng, vocab):
+    """Graft the known continuation into the GPU-drafted tree (host arrays of the C ABI)."""
+    def hook(eng, t):
+        n = eng.committed
+        k = n - n_prompt + 1
+        want = plan(n)
+        nn = t.n_nodes
+        tok, par = t.token, t.parent
+        cur, on_path = 0, {0}
+        for d in range(1, want + 1):
+            if k + d - 1 >= len(stream):
+                break
+            kids = [c for c in range(nn) if par[c] == cur]
+            if kids:
+                c = kids[int(rng.integers(len(kids)))]
+            else:
+                leaves = [c for c in range(cur + 1, nn) if c not in on_path and not any(par[x] == c for x in range(nn))]
+                if not leaves:
+                    break
+                c = leaves[int(rng.integers(len(leaves)))]
+                par[c] = cur
+            tok[c] = stream[k + d - 1]
+            cur = c
+            on_path.add(c)
+        for j in range(1, nn):
+            t.depth[j] = t.depth[par[j]] + 1
+        return t
+    return hook
+
+
+@pytest.mark.parametrize("want", [1, 2, 3])
+def test_tiny_fp32_forged_trees_accept_and_compact(env, tiny_gpu, want):
+    """Forged trees force acceptance lengths 1..D; output must stay the greedy stream, and the compacted
+    KV cache must equal the oracle's cache for the committed sequence."""
+    torch, P = env
+    sh, hw, w64, prompt, dw = tiny_gpu
+    gen = 40
+    greedy = oracle.greedy_decode(w64, sh, prompt, gen + 8)
+    eng = P.Engine(sh, dw)
+    rng = np.random.default_rng(want)
+    got, taus = eng.generate(prompt, gen, tree_hook=forge_hook(greedy, len(prompt), lambda n: want, rng, sh.vocab))
+    assert got == greedy[:gen]
+    assert max(taus) == want + 1 and min(taus) >= 1
+    n = eng.committed
+    seq = np.array(list(prompt) + greedy)[:n]
+    ref = oracle.KVCache(sh.n_layers, n, sh.n_kv_heads, sh.head_dim)
+    _, feats = oracle.target_forward(w64, sh, ref, seq, np.arange(n), list(range(n)), [list(range(i + 1)) for i in range(n)])
+    for l in range(sh.n_layers):
+        k, v = eng.kv(0, l, n)
+        assert np.abs(k - ref.k[l].reshape(n, -1)).max() < 1e-4
+        assert np.abs(v - ref.v[l].reshape(n, -1)).max() < 1e-4
+    # draft cache: one entry per committed token except the first, all from true target features
+    dref = oracle.KVCache(1, n + 1, sh.n_kv_heads, sh.head_dim)
+    pos = np.arange(1, n)
+    oracle.draft_forward(w64, sh, dref, feats[:-1], seq[1:], pos, list(pos), [list(range(1, p + 1)) for p in pos])
+    n_d = n - (taus[-1])                      # entries written by root steps so far: up to the last cycle's old n
+    k, v = eng.kv(1, 0, n_d)
+    assert np.abs(k - dref.k[0, 1:n_d + 1].reshape(n_d, -1)).max() < 1e-4
+    assert np.abs(v - dref.v[0, 1:n_d + 1].reshape(n_d, -1)).max() < 1e-4
+
+
+def test_tiny_fp32_sampling_matches_oracle_decisions(env, tiny_gpu):
+    """T = 1 with the shared counter-based RNG: same seed -> same tokens as the oracle."""
+    torch, P = env
+    sh, hw, w64, prompt, dw = tiny_gpu
+    for seed in (1, 2):
+        eng = P.Engine(sh, dw, temperature=1.0, seed=seed)
+        got, gt = eng.generate(prompt, 24)
+        want, wt = oracle.spec_decode(w64, sh, prompt, 24, temperature=1.0, seed=seed)
+        assert got == want and gt == wt
+
+
+def test_tiny_fp32_sampling_accept_matches_oracle_on_forged_peaky_tree(env, tiny_gpu):
+    """Rejection sampling where acceptance actually happens: verify an oracle-forged tree whose children carry
+    the target's most probable tokens, at a low temperature, for several seeds."""
+    torch, P = env
+    sh, hw, w64, prompt, dw = tiny_gpu
+    temp = 0.05
+    accepted_any = False
+    for seed in range(6):
+        st, first = oracle.prefill(w64, sh, prompt, 128, temp, seed)
+        st.cycle = 1
+        t = oracle.draft_tree(st, sh.tree_depth, sh.tree_topk, sh.tree_total)
+        # first pass to learn the target's favourites, then plant them as children of the root and of node 1
+        lg, _ = oracle.verify_tree(st, t)
+        fav0 = oracle.top_k(lg[0], 3)
+        kids0 = t.children(0)[:3]
+        for c, v in zip(kids0, fav0):
+            t.token[c] = v
+        lg, ft = oracle.verify_tree(st, t)
+        acc, bonus = oracle.accept_sample(t, lg, temp, seed, 1)
+        eng = P.Engine(sh, dw, temperature=temp, seed=seed)
+        assert eng.prefill(prompt) == first
+        eng.draft_tree()
+        g = oracle_tree_to_gpu(P, t, sh.tree_total)
+        eng.verify(g)
+        out = eng.accept(g)
+        assert out == [int(t.token[j]) for j in acc] + [bonus]
+        accepted_any |= len(acc) > 0
+    assert accepted_any
+
+
+BF16_TRUNC = wl.LLAMA2_7B.with_(name="llama2-7b-2layer", n_layers=2, prompt_len=96, gen_tokens=24)
+BF16_GQA = wl.LLAMA3_8B.with_(name="llama3-8b-width-2layer", n_layers=2, vocab=8192, d_ffn=4096, prompt_len=300, gen_tokens=16)
+
+
+@pytest.fixture(scope="module", params=[BF16_TRUNC, BF16_GQA], ids=lambda s: s.name)
+def bf16_model(request, env):
+    torch, P = env
+    sh = request.param
+    hw = wl.make_weights(sh)
+    return sh, hw, P.upload_weights(hw, sh.dtype), wl.make_prompt(sh)
+
+
+def test_bf16_logits_within_tolerance_of_oracle(env, bf16_model):
+    """Real widths, two layers: GPU bf16 logits of a verified tree against the oracle on the same tree.
+
+    (1) Against the oracle evaluated with the configuration's storage type (activations held in bf16 between
+        operations, as the configuration defines): every logit within 3e-2 + 2e-2 |ref|.
+    (2) Against the plain fp32 oracle: the same bound holds for at least 99 % of the logits and the error stays
+        within what bf16 storage of the cached keys/values and of the GEMM inputs must produce (rms < 0.02,
+        max < 0.12 at logit sigma 1.3); the derivation is in the design notes."""
+    torch, P = env
+    sh, hw, dw, prompt = bf16_model
+    eng = P.Engine(sh, dw)
+    first = eng.prefill(prompt)
+    t = eng.draft_tree()
+    eng.verify(t)
+    got = eng.logits(t.n_nodes)
+    w32 = as_dtype(hw, np.float32)
+    for store, strict in ((wl.round_to_bf16, True), (None, False)):
+        st, ofirst = oracle.prefill(w32, sh, prompt, len(prompt) + 200, dtype=np.float32, store=store)
+        ot = oracle.Tree(t.token[:t.n_nodes].copy(), t.parent[:t.n_nodes].copy(), t.depth[:t.n_nodes].copy(), t.score[:t.n_nodes].copy())
+        ot.token[0] = first                   # compare on the GPU's root token even if a near-tie flipped the oracle's
+        want, _ = oracle.verify_tree(st, ot)
+        err = np.abs(got - want)
+        ok = err <= 3e-2 + 2e-2 * np.abs(want)
+        print(f"{sh.name} store={'bf16' if store else 'fp32'}: max err {err.max():.4f} rms {np.sqrt((err ** 2).mean()):.4f} "
+              f"within tolerance {ok.mean() * 100:.3f} %")
+        if strict:
+            assert ok.all(), f"max abs err {err.max()}"
+        else:
+            assert ok.mean() >= 0.99 and err.max() < 0.12 and np.sqrt((err ** 2).mean()) < 0.02
+
+
+def test_bf16_spec_equals_greedy_bit_exact(env, bf16_model):
+    """GPU speculative decoding == GPU plain decoding, token for token and logit bit for logit bit,
+    with the real (random) draft and with forged trees that force acceptance."""
+    torch, P = env
+    sh, hw, dw, prompt = bf16_model
+    gen = sh.gen_tokens
+    plain = P.Engine(sh, dw, tree=(1, 1, 1))
+    prec = []
+    greedy, _ = plain.generate(prompt, gen + 8, record=prec)
+    spec = P.Engine(sh, dw)
+    got, taus = spec.generate(prompt, gen)
+    assert got == greedy[:gen]
+    rng = np.random.default_rng(0)
+    spec2 = P.Engine(sh, dw)
+    srec = []
+    got2, taus2 = spec2.generate(prompt, gen, tree_hook=forge_hook(greedy, len(prompt), lambda n: n % 5, rng, sh.vocab), record=srec)
+    assert got2 == greedy[:gen] and max(taus2) >= 4
+    # logits of the root row of every cycle == logits plain decoding produced at the same position, bit for bit
+    plain_at = {r["n"]: r["logits"][0] for r in prec}
+    for r in srec:
+        assert np.array_equal(r["logits"][0], plain_at[r["n"]])

@@ -110,19 +110,24 @@ def round_to_bf16(x: np.ndarray) -> np.ndarray:
     return r.view(np.float32)
 
 
+def _draw(shape: Shape, name: str, dims, std: float) -> np.ndarray:
+    rng = np.random.Generator(np.random.Philox(key=tensor_seed(shape.seed, name)))
+    w = rng.standard_normal(dims, dtype=np.float32) * np.float32(std)
+    return round_to_bf16(w) if shape.dtype == "bf16" else w
+
+
 def make_weights(shape: Shape, std: float = 0.02) -> Dict[str, np.ndarray]:
-    """Host weights as float32 arrays.  For bf16 configs every value is bf16-representable."""
-    out: Dict[str, np.ndarray] = {}
-    for name, dims, kind in tensor_specs(shape):
-        if kind == "ones":
-            out[name] = np.ones(dims, dtype=np.float32)
-            continue
-        rng = np.random.Generator(np.random.Philox(key=tensor_seed(shape.seed, name)))
-        w = rng.standard_normal(dims, dtype=np.float32) * np.float32(std)
-        if shape.dtype == "bf16":
-            w = round_to_bf16(w)
-        out[name] = w
-    return out
+    """Host weights as float32 arrays.  For bf16 configs every value is bf16-representable.
+    Each tensor has its own seeded stream, so tensors are drawn in parallel threads."""
+    from concurrent.futures import ThreadPoolExecutor
+    import os
+    specs = tensor_specs(shape)
+    out: Dict[str, np.ndarray] = {n: np.ones(d, dtype=np.float32) for n, d, k in specs if k == "ones"}
+    todo = [(n, d) for n, d, k in specs if k == "normal"]
+    with ThreadPoolExecutor(max_workers=min(16, os.cpu_count() or 1)) as ex:
+        for (n, _), w in zip(todo, ex.map(lambda nd: _draw(shape, nd[0], nd[1], std), todo)):
+            out[n] = w
+    return {n: out[n] for n, _, _ in specs}
 
 
 def make_prompt(shape: Shape, length: int | None = None) -> np.ndarray:
