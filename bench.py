@@ -95,7 +95,7 @@ def main():
     if a.layers:
         sh = sh.with_(n_layers=a.layers, name=f"{sh.name}-{a.layers}layer")
     torch.cuda.set_device(0)
-    weights = dict(wl.iter_device_weights(sh, "cuda"))
+    weights = P.pack_weights(wl.iter_device_weights(sh, "cuda"))
     prompt = wl.make_prompt(sh)
     total_cycles = a.warmup + a.steps
     max_seq = sh.prompt_len + (sh.tree_depth + 1) * total_cycles + sh.tree_total + 32

@@ -65,8 +65,10 @@ typedef struct spec_config {
 } spec_config;
 
 /* DEVICE pointers, BORROWED for the life of the context, never written.
- * Projection matrices are row-major [out, in] in the configured dtype; norm
- * weights are [d_model] in the configured dtype. */
+ * Projection matrices ([out, in], shapes in the comments) are in the library's
+ * PACKED layout, produced once at load time by spec_pack_weight(); the
+ * embedding table stays row-major (it is gathered by row); norm weights are
+ * [d_model] vectors.  All in the configured dtype. */
 typedef struct spec_layer_weights {
   const void *attn_norm;
   const void *wq, *wk, *wv;   /* [n_q_heads*head_dim, d], [n_kv_heads*head_dim, d] x2 */
@@ -77,11 +79,11 @@ typedef struct spec_layer_weights {
 } spec_layer_weights;
 
 typedef struct spec_weights {
-  const void *embed;                 /* [vocab, d]; shared by target and draft (Sec. 2)   */
-  const void *lm_head;               /* [vocab, d]; shared by target and draft            */
+  const void *embed;                 /* [vocab, d] row-major; shared by target and draft (Sec. 2) */
+  const void *lm_head;               /* [vocab, d] packed; shared by target and draft     */
   const void *final_norm;            /* [d]; its output is the feature given to the draft */
   const spec_layer_weights *layers;  /* HOST array of n_layers entries (device pointers)  */
-  const void *draft_fc;              /* [d, 2d]: concat(feature, embedding) -> d, no bias */
+  const void *draft_fc;              /* [d, 2d] packed: concat(feature, embedding) -> d, no bias */
   spec_layer_weights draft_layer;    /* the draft's single decoder layer                  */
 } spec_weights;
 
@@ -94,6 +96,20 @@ typedef struct spec_tree {
   int32_t *depth;    /* depth[0] = 0; depth[j] = depth[parent[j]] + 1 <= D       */
   float   *score;    /* cumulative draft log-probability; score[0] = 0; may be NULL on input */
 } spec_tree;
+
+/* Packed layout.  The weight-streaming kernels read 16-byte pieces in the order
+ * the matrix cores consume them, so that one wavefront-wide load covers 1 KiB of
+ * consecutive bytes.  A row-major [rows, in] matrix is cut into tiles of 32 rows
+ * x 256 bytes of k; tiles of one 32-row block follow each other along k; inside
+ * a tile piece (j = 0..7, lane = 0..63) is at byte j*1024 + lane*16 and holds row
+ * lane%32, k-bytes (lane/32)*128 + j*16 .. +16 of the tile.  Rows and k are
+ * zero-padded to whole tiles.
+ *   spec_packed_bytes : size of the packed form (host-only computation; 0 if bad).
+ *   spec_pack_weight  : out-of-place repack, DEVICE src (row-major) -> DEVICE dst
+ *                       (256-byte aligned, spec_packed_bytes large), enqueued on
+ *                       `stream`; src and dst must not overlap. */
+uint64_t spec_packed_bytes(int32_t dtype, int32_t rows, int32_t in);
+int spec_pack_weight(int32_t dtype, const void *src, int32_t rows, int32_t in, void *dst, void *stream);
 
 /* Bytes of device workspace a context with this configuration needs (0 if the
  * configuration is invalid).  Host-only computation. */

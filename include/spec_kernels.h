@@ -20,8 +20,8 @@ extern "C" {
  * gate/up, down, draft fc, LM head; target forward of Sec. 2's "evaluates ...
  * in parallel" step):   part[s][i][c] = sum over the s-th K range of
  * x[i][k] * w[c][k].  Up to three weight matrices (w0, w1, w2; rows0..2 rows
- * each, row-major [rows, in]; unused ones NULL / 0) share x and write
- * consecutive column ranges.  x: [m, in] with row stride ldx elements,
+ * each, [rows, in] in the PACKED layout of spec_pack_weight; unused ones
+ * NULL / 0) share x and write consecutive column ranges.  x: [m, in] with row stride ldx elements,
  * 1 <= m <= 128.  part: fp32 [n_split][m_pad][ldp], ldp >= rows0+rows1+rows2,
  * m_pad >= m.  The K ranges are whole slabs (256 bf16 / 128 fp32 elements),
  * balanced to within one slab; the caller sums the splits in ascending order. */
@@ -35,7 +35,7 @@ int spec_k_gemm(int32_t dtype, const void *x, int32_t ldx, int32_t m, int32_t in
  * positions 0 .. base + depth[i]: position p < base is cache row p, position
  * p >= base is cache row base + anc[i*16 + p - base] (anc NULL: row p).
  * kcache, vcache: [*, hkv*hd].  out: [rows, hq*hd] in dtype.  scratch: fp32,
- * rows*hq*max_parts*(hd+2) floats with max_parts >= (base+max depth)/256 + 1.
+ * rows*hq*max_parts*(hd+2) floats with max_parts >= (base+max depth)/256 + 2.
  * hd must be 64 or 128, hq/hkv one of 1, 2, 4, 8. */
 int spec_k_attention(int32_t dtype, const void *q, const void *kcache, const void *vcache, int32_t rows, int32_t hq,
                      int32_t hkv, int32_t hd, int32_t base, const int32_t *depth, const int32_t *anc, int32_t max_depth,

@@ -75,6 +75,9 @@ lib.spec_set_profile.argtypes = [C.c_void_p, C.c_int32]
 lib.spec_get_profile.argtypes = [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_int64)]
 lib.spec_last_error.restype = C.c_char_p
 lib.spec_last_error.argtypes = [C.c_void_p]
+lib.spec_packed_bytes.restype = C.c_uint64
+lib.spec_packed_bytes.argtypes = [C.c_int32, C.c_int32, C.c_int32]
+lib.spec_pack_weight.argtypes = [C.c_int32, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
 lib.spec_k_gemm.argtypes = [C.c_int32, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_int32, C.c_void_p,
                             C.c_int32, C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p]
 lib.spec_k_attention.argtypes = [C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
@@ -195,13 +198,42 @@ def _stream_ptr(stream=None):
     return C.c_void_p(s.cuda_stream)
 
 
+def spec_packed_bytes(dtype: int, rows: int, cols: int) -> int:
+    return int(lib.spec_packed_bytes(dtype, rows, cols))
+
+
+def spec_pack_weight(w):
+    """Row-major torch matrix [rows, in] on the device -> packed copy (uint8 tensor that remembers its shape)."""
+    import torch
+    assert w.is_contiguous() and w.dim() == 2
+    dtype = 1 if w.dtype == torch.bfloat16 else 0
+    n = spec_packed_bytes(dtype, w.shape[0], w.shape[1])
+    if n == 0:
+        raise SpecError(SPEC_EINVAL, f"cannot pack a {tuple(w.shape)} {w.dtype} matrix")
+    dst = torch.empty(n, dtype=torch.uint8, device=w.device)
+    rc = lib.spec_pack_weight(dtype, w.data_ptr(), w.shape[0], w.shape[1], dst.data_ptr(), _stream_ptr())
+    if rc:
+        raise SpecError(rc, "spec_pack_weight")
+    dst.logical_shape = tuple(w.shape)
+    return dst
+
+
+PACKED_TENSORS = ("wq", "wk", "wv", "wo", "w_gate", "w_up", "w_down", "lm_head", "fc")
+
+
+def is_packed_name(name: str) -> bool:
+    return name.rsplit(".", 1)[-1] in PACKED_TENSORS
+
+
 def spec_k_gemm(x, ws: Sequence, n_split: int, m: Optional[int] = None):
-    """x: torch [m, in]; ws: 1..3 torch weight matrices [rows, in].  Returns fp32 torch [n_split, m, cols]."""
+    """x: torch [m, in]; ws: 1..3 row-major torch weight matrices [rows, in] (packed here, per call: test use).
+    Returns fp32 torch [n_split, m, cols]."""
     import torch
     dtype = 1 if x.dtype == torch.bfloat16 else 0
     m = x.shape[0] if m is None else m
     rows = [w.shape[0] for w in ws] + [0] * (3 - len(ws))
-    ptrs = [C.c_void_p(w.data_ptr()) for w in ws] + [None] * (3 - len(ws))
+    packed = [spec_pack_weight(w.contiguous()) for w in ws]
+    ptrs = [C.c_void_p(w.data_ptr()) for w in packed] + [None] * (3 - len(ws))
     cols = sum(rows)
     part = torch.full((n_split, m, cols), float("nan"), dtype=torch.float32, device=x.device)
     rc = lib.spec_k_gemm(dtype, x.data_ptr(), x.stride(0), m, x.shape[1], ptrs[0], rows[0], ptrs[1], rows[1], ptrs[2], rows[2],
@@ -219,7 +251,7 @@ def spec_k_attention(q, kcache, vcache, base: int, depth, anc, hq: int, hkv: int
     dtype = 1 if kcache.dtype == torch.bfloat16 else 0
     rows = q.shape[0]
     max_depth = int(depth.max().item())
-    max_parts = (base + max_depth) // 256 + 1
+    max_parts = (base + max_depth) // 256 + 2
     scratch = torch.empty(rows * hq * max_parts * (hd + 2), dtype=torch.float32, device=q.device)
     out = torch.empty(q.shape, dtype=kcache.dtype, device=q.device)
     rc = lib.spec_k_attention(dtype, q.data_ptr(), kcache.data_ptr(), vcache.data_ptr(), rows, hq, hkv, hd, base,
@@ -245,11 +277,22 @@ def spec_k_topk_logprob(logits, k: int):
     return tok[:, :k], lp[:, :k]
 
 
+def pack_weights(named_tensors) -> Dict[str, "object"]:
+    """(name, row-major device tensor) pairs -> dict with every projection matrix in the packed layout.
+    Matrices are packed one at a time and the row-major original is dropped, so the peak extra memory
+    is one matrix."""
+    out = {}
+    for name, t in named_tensors:
+        out[name] = spec_pack_weight(t.contiguous()) if is_packed_name(name) else t.contiguous()
+        del t
+    return out
+
+
 def upload_weights(host: Dict[str, np.ndarray], dtype: str, device: str = "cuda") -> Dict[str, "object"]:
-    """numpy float32 weights -> torch tensors on the device in the storage type (plumbing only)."""
+    """numpy float32 weights -> device tensors in the storage type, projections packed (plumbing only)."""
     import torch
     tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
-    return {k: torch.from_numpy(np.ascontiguousarray(v)).to(device=device, dtype=tdt).contiguous() for k, v in host.items()}
+    return pack_weights((k, torch.from_numpy(np.ascontiguousarray(v)).to(device=device, dtype=tdt)) for k, v in host.items())
 
 
 class Engine:

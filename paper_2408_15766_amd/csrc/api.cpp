@@ -160,7 +160,7 @@ size_t layout(const spec_config &c, spec_ctx *x, char *base) {
   const int m_max = std::max({c.tree_total, kPrefillChunk, kMaxDepth + 1, c.tree_topk});
   const int k = std::max(1, c.tree_topk), D = std::max(1, c.tree_depth);
   const int seq_draft = c.max_seq + D * k;
-  const int max_parts = (c.max_seq + D * k) / kAttnPart + 1;
+  const int max_parts = (c.max_seq + D * k) / kAttnPart + 2;   // parts of the longest row + the tail slot
   size_t part_floats = 0;
   {
     struct { int rows, in; } g[5] = {{dq + 2 * dkv, d}, {d, dq}, {2 * f, d}, {d, f}, {d, 2 * d}};
@@ -394,6 +394,16 @@ int sync(spec_ctx *c) {
 
 // =============================================================================================
 extern "C" {
+
+uint64_t spec_packed_bytes(int32_t dtype, int32_t rows, int32_t in) {
+  if ((dtype != 0 && dtype != 1) || rows < 1 || in < 1 || in % (dtype == 1 ? 8 : 4)) return 0;
+  return packed_weight_bytes(dtype, rows, in);
+}
+
+int spec_pack_weight(int32_t dtype, const void *src, int32_t rows, int32_t in, void *dst, void *stream) {
+  if (!src || !dst || spec_packed_bytes(dtype, rows, in) == 0 || ((uintptr_t)dst & 15) || ((uintptr_t)src & 15)) return SPEC_EINVAL;
+  return launch_pack_weight(dtype, src, rows, in, dst, (hipStream_t)stream) == hipSuccess ? SPEC_OK : SPEC_EHIP;
+}
 
 uint64_t spec_workspace_bytes(const spec_config *cfg) {
   if (!config_ok(cfg, nullptr)) return 0;

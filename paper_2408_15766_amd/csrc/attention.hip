@@ -9,11 +9,27 @@
 // a function of (its query, the key/value rows by position) only, so speculative and
 // plain decoding agree bit for bit.
 //
-// One wavefront handles (row, kv head, part of kAttnPart = 256 key positions) and all G
-// query heads that share the kv head.  Parts have fixed absolute boundaries; within a part
-// keys are taken 64 at a time, lane = position offset, with wave shuffles for the running
-// max and sum of the online softmax; P*V is accumulated key by key in position order.  A
-// second kernel merges the parts of a row in ascending order.
+// Two code paths share one definition of the key order:
+//
+//  * vector path (attn_part_kernel): one wavefront handles (row, kv head, part of kAttnPart = 256
+//    key positions) and all G query heads that share the kv head; keys are taken 64 at a time,
+//    lane = position offset, wave shuffles give the running max and sum of the online softmax,
+//    P*V is accumulated key by key in position order.  Used for fp32 storage, and for the TAIL
+//    of every row in bf16 storage.
+//
+//  * matrix-core path (attn_bulk_kernel, bf16 storage): the BULK of a row's keys, positions
+//    [0, A(p)) with A(p) = 32 * floor(max(p - kMaxDepth, 0) / 32), lies in the committed cache
+//    for every row of a tree (depth <= kMaxDepth), is the same key set for spec and plain decoding,
+//    and is shared by all rows, so it runs as dense 32-key blocks on the MFMA units: S^T = K Q^T
+//    and O^T = V^T P^T with v_mfma_f32_32x32x16_bf16, K/V blocks staged once in LDS for all rows
+//    (V transposed on the way in), queries and probabilities split into bf16 hi + lo parts so
+//    that they keep fp32-class accuracy.  The remaining positions [A(p), p] (16..47 keys: the end
+//    of the cache plus the row's own path) take the vector path.  A(p) depends on the position
+//    only, so a row is computed by the same instructions over the same key groups whether it is
+//    alone or part of a tree.
+//
+// Parts (fixed absolute boundaries, kAttnPart positions) are merged per row in ascending order by
+// attn_combine_kernel, the tail last.
 #include "common.h"
 #include "kernels.h"
 
@@ -38,6 +54,9 @@ template <> struct Chunk<bf16_t> {
   }
 };
 
+// End of the bulk region of a row at position p (a multiple of 32, <= p - kMaxDepth): see the header.
+__device__ __host__ __forceinline__ int bulk_end(int p) { return p > kMaxDepth ? ((p - kMaxDepth) / 32) * 32 : 0; }
+
 template <typename T, int HD, int G>
 __global__ __launch_bounds__(64) void attn_part_kernel(AttnArgs a) {
   constexpr int EPL = Chunk<T>::kEpl;
@@ -45,9 +64,11 @@ __global__ __launch_bounds__(64) void attn_part_kernel(AttnArgs a) {
   __shared__ __attribute__((aligned(16))) float qs[G][HD];
   const int i = blockIdx.x, hk = blockIdx.y, part = blockIdx.z, lane = threadIdx.x;
   const int p = a.base + a.depth[i];
-  const int k_lo = part * kAttnPart;
-  const int k_hi = min(p + 1, k_lo + kAttnPart);
+  // full mode: part `part` of the whole range [0, p]; tail mode: the single range [A(p), p]
+  const int k_lo = a.tail_only ? bulk_end(p) : part * kAttnPart;
+  const int k_hi = a.tail_only ? p + 1 : min(p + 1, k_lo + kAttnPart);
   if (k_lo >= k_hi) return;
+  const int part_slot = a.tail_only ? a.max_parts - 1 : part;
 
   const float *qrow = (const float *)a.q + ((size_t)i * a.hq + (size_t)hk * G) * HD;   // queries are fp32
   for (int e = lane; e < G * HD; e += 64) qs[e / HD][e % HD] = qrow[e];
@@ -113,7 +134,7 @@ __global__ __launch_bounds__(64) void attn_part_kernel(AttnArgs a) {
   }
 #pragma unroll
   for (int gh = 0; gh < G; gh++) {
-    float *dst = a.part + (((size_t)i * a.hq + hk * G + gh) * a.max_parts + part) * (HD + 2);
+    float *dst = a.part + (((size_t)i * a.hq + hk * G + gh) * a.max_parts + part_slot) * (HD + 2);
     if (lane == 0) { dst[0] = m_run[gh]; dst[1] = l_run[gh]; }
 #pragma unroll
     for (int dd = 0; dd < DPL; dd++) dst[2 + lane * DPL + dd] = o[gh][dd];
@@ -125,10 +146,12 @@ template <typename T, int HD>
 __global__ void attn_combine_kernel(AttnArgs a) {
   const int i = blockIdx.x, h = blockIdx.y, d = threadIdx.x;
   const int p = a.base + a.depth[i];
-  const int n_parts = p / kAttnPart + 1;
+  // full mode: parts 0 .. p/256; hybrid mode: the bulk parts that hold keys of this row, then the tail slot
+  const int n_parts = a.tail_only ? (bulk_end(p) + kAttnPart - 1) / kAttnPart : p / kAttnPart + 1;
   const float *src = a.part + ((size_t)i * a.hq + h) * a.max_parts * (HD + 2);
-  float m = src[0];
-  for (int t = 1; t < n_parts; t++) m = fmaxf(m, src[(size_t)t * (HD + 2)]);
+  const float *tail = src + (size_t)(a.max_parts - 1) * (HD + 2);
+  float m = a.tail_only ? tail[0] : -INFINITY;
+  for (int t = 0; t < n_parts; t++) m = fmaxf(m, src[(size_t)t * (HD + 2)]);
   float l = 0.f, o = 0.f;
   for (int t = 0; t < n_parts; t++) {
     const float *s = src + (size_t)t * (HD + 2);
@@ -136,24 +159,215 @@ __global__ void attn_combine_kernel(AttnArgs a) {
     l += s[1] * w;
     o += s[2 + d] * w;
   }
+  if (a.tail_only) {
+    const float w = expf(tail[0] - m);
+    l += tail[1] * w;
+    o += tail[2 + d] * w;
+  }
   ((T *)a.out)[((size_t)i * a.hq + h) * HD + d] = from_f32<T>(o / l);
 }
 
+// ---- matrix-core path for the bulk region (bf16 storage) -----------------------------------
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
+typedef __attribute__((ext_vector_type(16))) float f32x16_t;
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2_t;
+
+// x = hi + lo with hi, lo bf16: the pair keeps ~16 mantissa bits of an fp32 value.
+__device__ __forceinline__ void split_bf16(float x, uint32_t &hi, uint32_t &lo) {
+  hi = f32_to_bf16_bits(x);
+  lo = f32_to_bf16_bits(x - bf16_bits_to_f32(hi));
+}
+__device__ __forceinline__ void split8(const float (&x)[8], u32x4_t &hi, u32x4_t &lo) {
+  uint32_t h[8], l[8];
+#pragma unroll
+  for (int e = 0; e < 8; e++) split_bf16(x[e], h[e], l[e]);
+  hi = u32x4_t{h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16)};
+  lo = u32x4_t{l[0] | (l[1] << 16), l[2] | (l[3] << 16), l[4] | (l[5] << 16), l[6] | (l[7] << 16)};
+}
+__device__ __forceinline__ f32x16_t mfma_bf16(const u32x4_t &a, const u32x4_t &b, f32x16_t c) {
+  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, a), __builtin_bit_cast(bf16x8_t, b), c, 0, 0, 0);
+}
+
+constexpr int kBulkBlocksPerPart = kAttnPart / 32;
+
+// grid (parts, kv heads, groups of NW query blocks); block NW waves.  Wave w owns 32 "query rows"
+// (row i, head gh of the kv group), r = qblock*32 + lane%32, i = r / G, gh = r % G.
+template <int HD, int G, int NW>
+__global__ __launch_bounds__(NW * 64) void attn_bulk_kernel(AttnArgs a) {
+  constexpr int DB = HD / 32;                 // 32-dim blocks of the output
+  constexpr int KK = HD / 16;                 // MFMA steps of q.k
+  constexpr int KSTR = HD * 2 + 16;           // LDS bytes per key row (+16: conflict-free b128 reads)
+  constexpr int VSTR = 32 * 2 + 8;            // LDS bytes per dim row of V^T (+8: conflict-free b64 reads)
+  constexpr int NT = NW * 64;
+  constexpr int PIECES = (32 * HD * 2 / 16 + NT - 1) / NT;   // 16-byte pieces of one K (or V) block per thread
+  __shared__ __attribute__((aligned(16))) unsigned char k_lds[32 * KSTR];
+  __shared__ __attribute__((aligned(16))) unsigned char vt_lds[HD * VSTR];
+
+  const int part = blockIdx.x, hk = blockIdx.y;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, c = lane & 31, g = lane >> 5;
+  const int b_lo = part * kBulkBlocksPerPart;
+  const int b_hi = min(b_lo + kBulkBlocksPerPart, a.bulk_blocks);
+  if (b_lo >= b_hi) return;
+
+  const int r = (blockIdx.z * NW + wave) * 32 + c;
+  const bool valid_q = r < a.rows * G;
+  const int i = valid_q ? r / G : 0, gh = valid_q ? r % G : 0;
+  const int n_incl = valid_q ? bulk_end(a.base + a.depth[i]) / 32 : 0;      // blocks [0, n_incl) belong to this row
+
+  // query fragments: step kk covers dims kk*16 + g*8 .. +8
+  u32x4_t qhi[KK], qlo[KK];
+  {
+    const float *qrow = (const float *)a.q + ((size_t)i * a.hq + (size_t)hk * G + gh) * HD;
+#pragma unroll
+    for (int kk = 0; kk < KK; kk++) {
+      float x[8];
+      const float4 x0 = *(const float4 *)(qrow + kk * 16 + g * 8), x1 = *(const float4 *)(qrow + kk * 16 + g * 8 + 4);
+      x[0] = x0.x; x[1] = x0.y; x[2] = x0.z; x[3] = x0.w; x[4] = x1.x; x[5] = x1.y; x[6] = x1.z; x[7] = x1.w;
+      split8(x, qhi[kk], qlo[kk]);
+    }
+  }
+  f32x16_t o[DB];
+#pragma unroll
+  for (int db = 0; db < DB; db++)
+#pragma unroll
+    for (int v = 0; v < 16; v++) o[db][v] = 0.f;
+  float m_run = -INFINITY, l_run = 0.f;
+
+  const size_t row_stride = (size_t)a.hkv * HD;              // elements between consecutive cache slots
+  const bf16_t *kg = (const bf16_t *)a.kcache + (size_t)hk * HD;
+  const bf16_t *vg = (const bf16_t *)a.vcache + (size_t)hk * HD;
+  constexpr int PPR = HD * 2 / 16;                           // pieces per key row
+  u32x4_t kreg[PIECES], vreg[PIECES];
+  auto prefetch = [&](int b) {
+#pragma unroll
+    for (int e = 0; e < PIECES; e++) {
+      const int q = tid + e * NT;
+      const int key = (q / PPR) & 31, piece = q % PPR;       // (& 31: threads past the block re-read a valid key)
+      const size_t off = (size_t)(b * 32 + key) * row_stride + piece * 8;
+      kreg[e] = *(const u32x4_t *)(kg + off);
+      vreg[e] = *(const u32x4_t *)(vg + off);
+    }
+  };
+  auto stage = [&]() {
+#pragma unroll
+    for (int e = 0; e < PIECES; e++) {
+      const int q = tid + e * NT;
+      if (q < 32 * PPR) {
+        const int key = q / PPR, piece = q % PPR;
+        *(u32x4_t *)(k_lds + key * KSTR + piece * 16) = kreg[e];
+        const uint32_t w[4] = {vreg[e].x, vreg[e].y, vreg[e].z, vreg[e].w};
+#pragma unroll
+        for (int d2 = 0; d2 < 8; d2++)                       // V^T[dim][key]
+          *(uint16_t *)(vt_lds + (piece * 8 + d2) * VSTR + key * 2) = (uint16_t)(w[d2 >> 1] >> ((d2 & 1) * 16));
+      }
+    }
+  };
+
+  prefetch(b_lo);
+  for (int b = b_lo; b < b_hi; b++) {
+    __syncthreads();                                         // every wave is done reading the previous block
+    stage();
+    __syncthreads();
+    if (b + 1 < b_hi) prefetch(b + 1);
+
+    f32x16_t s;
+#pragma unroll
+    for (int v = 0; v < 16; v++) s[v] = 0.f;
+#pragma unroll
+    for (int kk = 0; kk < KK; kk++) {
+      const u32x4_t kf = *(const u32x4_t *)(k_lds + c * KSTR + kk * 32 + g * 16);
+      s = mfma_bf16(kf, qhi[kk], s);
+      s = mfma_bf16(kf, qlo[kk], s);
+    }
+    // s[v] = q . k for key 8*(v/4) + 4*g + v%4 of the block and query row c
+    const bool incl = b < n_incl;
+    float mb = -INFINITY;
+#pragma unroll
+    for (int v = 0; v < 16; v++) { s[v] = incl ? s[v] * a.scale : -INFINITY; mb = fmaxf(mb, s[v]); }
+    mb = fmaxf(mb, __shfl_xor(mb, 32, 64));
+    const float m_new = fmaxf(m_run, mb);
+    const float corr = m_new == -INFINITY ? 1.f : expf(m_run - m_new);
+    float pv[16], ls = 0.f;
+#pragma unroll
+    for (int v = 0; v < 16; v++) { pv[v] = incl ? expf(s[v] - m_new) : 0.f; ls += pv[v]; }
+    ls += __shfl_xor(ls, 32, 64);
+    l_run = l_run * corr + ls;
+    m_run = m_new;
+#pragma unroll
+    for (int db = 0; db < DB; db++)
+#pragma unroll
+      for (int v = 0; v < 16; v++) o[db][v] *= corr;
+    // O^T += V^T P^T over two 16-key steps; step t uses the lane's own values v = 8t .. 8t+7,
+    // i.e. keys 16t + 8*(e/4) + 4g + e%4, and V^T supplies the same keys per dim.
+#pragma unroll
+    for (int t = 0; t < 2; t++) {
+      float x[8];
+#pragma unroll
+      for (int e = 0; e < 8; e++) x[e] = pv[8 * t + e];
+      u32x4_t phi, plo;
+      split8(x, phi, plo);
+#pragma unroll
+      for (int db = 0; db < DB; db++) {
+        const unsigned char *vp = vt_lds + (db * 32 + c) * VSTR + (16 * t + 4 * g) * 2;
+        const u32x2_t v0 = *(const u32x2_t *)vp, v1 = *(const u32x2_t *)(vp + 16);
+        const u32x4_t vf = {v0.x, v0.y, v1.x, v1.y};
+        o[db] = mfma_bf16(vf, phi, o[db]);
+        o[db] = mfma_bf16(vf, plo, o[db]);
+      }
+    }
+  }
+  if (!valid_q) return;
+  float *dst = a.part + (((size_t)i * a.hq + hk * G + gh) * a.max_parts + part) * (HD + 2);
+  if (g == 0) { dst[0] = m_run; dst[1] = l_run; }
+#pragma unroll
+  for (int db = 0; db < DB; db++)
+#pragma unroll
+    for (int v = 0; v < 16; v++) dst[2 + db * 32 + 8 * (v >> 2) + 4 * g + (v & 3)] = o[db][v];
+}
+
+template <int HD, int G, int NW>
+static hipError_t launch_bulk(const AttnArgs &a, int n_bulk_parts, int q_groups, hipStream_t st) {
+  hipLaunchKernelGGL((attn_bulk_kernel<HD, G, NW>), dim3(n_bulk_parts, a.hkv, q_groups), dim3(NW * 64), 0, st, a);
+  return hipGetLastError();
+}
+
 template <typename T, int HD, int G>
-static hipError_t launch_thg(const AttnArgs &a, int n_parts, hipStream_t st) {
-  hipLaunchKernelGGL((attn_part_kernel<T, HD, G>), dim3(a.rows, a.hkv, n_parts), dim3(64), 0, st, a);
-  hipError_t e = hipGetLastError();
+static hipError_t launch_thg(AttnArgs a, int max_pos, hipStream_t st) {
+  hipError_t e;
+  if (sizeof(T) == 2) {
+    // hybrid: matrix-core bulk over [0, A(max_pos)) + vector tail per row
+    a.tail_only = 1;
+    a.bulk_blocks = bulk_end(max_pos) / 32;
+    const int n_bulk_parts = (a.bulk_blocks + kBulkBlocksPerPart - 1) / kBulkBlocksPerPart;
+    if (n_bulk_parts + 1 > a.max_parts) return hipErrorInvalidValue;
+    if (n_bulk_parts > 0) {
+      const int qblocks = (a.rows * G + 31) / 32;
+      if (qblocks <= 1) e = launch_bulk<HD, G, 1>(a, n_bulk_parts, 1, st);
+      else if (qblocks <= 2) e = launch_bulk<HD, G, 2>(a, n_bulk_parts, 1, st);
+      else if (qblocks <= 4) e = launch_bulk<HD, G, 4>(a, n_bulk_parts, 1, st);
+      else e = launch_bulk<HD, G, 8>(a, n_bulk_parts, (qblocks + 7) / 8, st);
+      if (e != hipSuccess) return e;
+    }
+    hipLaunchKernelGGL((attn_part_kernel<T, HD, G>), dim3(a.rows, a.hkv, 1), dim3(64), 0, st, a);
+  } else {
+    a.tail_only = 0;
+    a.bulk_blocks = 0;
+    const int n_parts = max_pos / kAttnPart + 1;
+    if (n_parts > a.max_parts) return hipErrorInvalidValue;
+    hipLaunchKernelGGL((attn_part_kernel<T, HD, G>), dim3(a.rows, a.hkv, n_parts), dim3(64), 0, st, a);
+  }
+  e = hipGetLastError();
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL((attn_combine_kernel<T, HD>), dim3(a.rows, a.hq), dim3(HD), 0, st, a);
   return hipGetLastError();
 }
 template <typename T, int HD>
-static hipError_t launch_th(const AttnArgs &a, int n_parts, hipStream_t st) {
+static hipError_t launch_th(const AttnArgs &a, int max_pos, hipStream_t st) {
   switch (a.hq / a.hkv) {
-    case 1: return launch_thg<T, HD, 1>(a, n_parts, st);
-    case 2: return launch_thg<T, HD, 2>(a, n_parts, st);
-    case 4: return launch_thg<T, HD, 4>(a, n_parts, st);
-    case 8: return launch_thg<T, HD, 8>(a, n_parts, st);
+    case 1: return launch_thg<T, HD, 1>(a, max_pos, st);
+    case 2: return launch_thg<T, HD, 2>(a, max_pos, st);
+    case 4: return launch_thg<T, HD, 4>(a, max_pos, st);
+    case 8: return launch_thg<T, HD, 8>(a, max_pos, st);
     default: return hipErrorInvalidValue;
   }
 }
@@ -161,10 +375,8 @@ static hipError_t launch_th(const AttnArgs &a, int n_parts, hipStream_t st) {
 // max_pos: largest key position any row attends to (host-known bound: base + max depth).
 hipError_t launch_attention(int dtype, const AttnArgs &a, int max_pos, hipStream_t st) {
   if (a.rows < 1 || a.hkv < 1 || a.hq % a.hkv != 0) return hipErrorInvalidValue;
-  const int n_parts = max_pos / kAttnPart + 1;
-  if (n_parts > a.max_parts) return hipErrorInvalidValue;
-  if (a.hd == 128) return dtype == 1 ? launch_th<bf16_t, 128>(a, n_parts, st) : launch_th<float, 128>(a, n_parts, st);
-  if (a.hd == 64) return dtype == 1 ? launch_th<bf16_t, 64>(a, n_parts, st) : launch_th<float, 64>(a, n_parts, st);
+  if (a.hd == 128) return dtype == 1 ? launch_th<bf16_t, 128>(a, max_pos, st) : launch_th<float, 128>(a, max_pos, st);
+  if (a.hd == 64) return dtype == 1 ? launch_th<bf16_t, 64>(a, max_pos, st) : launch_th<float, 64>(a, max_pos, st);
   return hipErrorInvalidValue;
 }
 

@@ -13,9 +13,17 @@
 //   B operand = 32 weight rows  x k-slice   (straight from global memory)
 //   D         = lane (c = lane%32, g = lane/32) holds weight row c of the
 //               wave's 32-row block for tokens 8*(v/4) + 4*g + v%4, v = 0..15
-// Lane (c, g) loads 128 contiguous bytes of weight row c per iteration (eight
-// 16-byte loads); the k indices of one MFMA are therefore not contiguous, which
-// is harmless because A and B are indexed by the same (g, element) pair.
+// Weights are read in the library's PACKED layout (pack_weight_kernel below): the
+// matrix is cut into tiles of 32 rows x KI k-elements (8 KiB; KI = 128 bf16 / 64 fp32),
+// tiles of one 32-row block are consecutive along k, and inside a tile the 16-byte piece
+// that lane (c, g) needs for MFMA step j sits at byte j*1024 + lane*16.  One wave-wide
+// load instruction therefore reads 1 KiB of consecutive bytes (eight full cache lines),
+// and a wave streams one contiguous region from start to end: measured on MI355X this
+// is worth ~1.4x in achieved HBM bandwidth over reading the same 16-byte pieces from a
+// row-major matrix (64 partial lines per instruction).  Piece (c, g, j) of tile (rb, it)
+// holds W[rb*32 + c][it*KI + g*KI/2 + j*EPL .. + EPL), zero beyond the matrix, so neither
+// ragged rows nor a ragged K need a special path.  The k indices of one MFMA are not
+// contiguous, which is harmless because A and B are indexed by the same (g, element) pair.
 //
 // Each wave owns one 32-row block of W for the workgroup's K range and all
 // token blocks; the four waves of a workgroup share the X slab.  Weight loads
@@ -26,6 +34,8 @@
 // W and the K split, never on M, on the position of the row in its tile or on
 // other rows, so a token computes bit-identical results alone (plain decoding)
 // or inside a tree.
+#include <algorithm>
+
 #include "common.h"
 #include "kernels.h"
 
@@ -41,6 +51,7 @@ constexpr int kLaneBytes = 128;                     // contiguous weight bytes p
 constexpr int kSlabIters = 2;                       // iterations per LDS slab
 constexpr int kSlabRowBytes = 2 * kLaneBytes * kSlabIters;   // 512 B of k per token row per slab
 constexpr int kSlabStride = kSlabRowBytes + 16;     // +16 B: conflict-free 16-byte LDS reads
+constexpr int kTileBytes = 32 * 2 * kLaneBytes;     // one packed tile: 32 rows x 256 B of k
 
 template <typename T> struct GemmTraits;
 template <> struct GemmTraits<bf16_t> { static constexpr int kEpl = 8; };   // elements per 16 bytes
@@ -68,7 +79,7 @@ __global__ __launch_bounds__(kGemmThreads, TB <= 2 ? 2 : 1) void gemm_stream_ker
   const int c = lane & 31, g = lane >> 5;
 
   // which 32-row block of which weight segment this wave streams (no dynamic indexing of the
-  // argument struct: that would push it to private memory)
+  // argument struct: that would push it to private memory).
   // A wave past the last block recomputes the last block and stores nothing, so that every wave
   // runs the same branch-free loop and the same barriers.
   const int blk_raw = blockIdx.x * kGemmWaves + wave;
@@ -81,16 +92,18 @@ __global__ __launch_bounds__(kGemmThreads, TB <= 2 ? 2 : 1) void gemm_stream_ker
   const int seg_col0 = seg == 0 ? a.seg_col0[0] : (seg == 1 ? a.seg_col0[1] : a.seg_col0[2]);
   const void *seg_w = seg == 0 ? a.seg_w[0] : (seg == 1 ? a.seg_w[1] : a.seg_w[2]);
   const int row = (blk - b0) * 32 + c;
-  const int row_c = min(row, seg_rows - 1);
-  const char *wrow = (const char *)seg_w + (size_t)row_c * (size_t)a.in * sizeof(T);
 
   // K splits are balanced to within one slab: split y covers slabs [y*S/n, (y+1)*S/n)
   constexpr int KSLAB = kSlabRowBytes / (int)sizeof(T);
-  const int n_slabs_total = (a.in + KSLAB - 1) / KSLAB;
-  const int k_begin = (int)((long long)blockIdx.y * n_slabs_total / a.n_split) * KSLAB;
-  const int k_end = min(a.in, (int)((long long)(blockIdx.y + 1) * n_slabs_total / a.n_split) * KSLAB);
-  const int n_iter = (k_end - k_begin + KI - 1) / KI;
+  const int n_it_total = (a.in + KI - 1) / KI;                         // tiles along k (K zero-padded to KI)
+  const int n_slabs_total = (n_it_total + kSlabIters - 1) / kSlabIters;
+  const int it_begin = (int)((long long)blockIdx.y * n_slabs_total / a.n_split) * kSlabIters;
+  const int it_end = min(n_it_total, (int)((long long)(blockIdx.y + 1) * n_slabs_total / a.n_split) * kSlabIters);
+  const int k_begin = it_begin * KI;
+  const int n_iter = it_end - it_begin;
   const int n_slab = (n_iter + kSlabIters - 1) / kSlabIters;
+  // this wave's stream: tiles it_begin .. it_end of row block (blk - b0), one contiguous region
+  const char *wstream = (const char *)seg_w + ((size_t)(blk - b0) * n_it_total + it_begin) * (size_t)kTileBytes + lane * 16;
 
   f32x16_t acc[TB];
 #pragma unroll
@@ -101,26 +114,14 @@ __global__ __launch_bounds__(kGemmThreads, TB <= 2 ? 2 : 1) void gemm_stream_ker
   u32x4_t ring[3][8];
   u32x4_t xr[XCH];
 
-  // Full iterations load without any guard, so nothing forces a wait between the load and its
-  // use two iterations later.  Only a ragged last iteration (K range not a multiple of KI) takes
-  // the guarded form, which zeroes the weight fragment beyond k_end; X never needs zeroing:
-  // out-of-range X addresses are clamped to valid finite data that meets a zero weight or a
-  // token row that is never stored.
-  const int n_full = (k_end - k_begin) / KI;
+  // Every tile is complete in the packed layout (zero-padded), so weight loads need no guard and
+  // nothing forces a wait between a load and its use two iterations later.  X never needs
+  // zeroing either: out-of-range X addresses are clamped to valid finite data that meets a zero
+  // weight or a token row that is never stored.
   auto load_w = [&](u32x4_t (&dst)[8], int it) {
-    const char *p = wrow + (size_t)(k_begin + it * KI + g * (KI / 2)) * sizeof(T);
+    const char *p = wstream + (size_t)it * kTileBytes;
 #pragma unroll
-    for (int j = 0; j < 8; j++) dst[j] = *(const u32x4_t *)(p + j * 16);
-  };
-  auto load_w_tail = [&](u32x4_t (&dst)[8], int it) {
-    const int k = k_begin + it * KI + g * (KI / 2);
-#pragma unroll
-    for (int j = 0; j < 8; j++) {
-      const int kk = k + j * EPL;
-      const bool ok = kk < k_end;
-      const u32x4_t v = *(const u32x4_t *)(wrow + (size_t)(ok ? kk : k_begin) * sizeof(T));
-      dst[j] = ok ? v : u32x4_t{0u, 0u, 0u, 0u};
-    }
+    for (int j = 0; j < 8; j++) dst[j] = *(const u32x4_t *)(p + j * 1024);
   };
   const char *xbase = (const char *)a.x;
   auto load_x = [&](int slab) {
@@ -130,7 +131,7 @@ __global__ __launch_bounds__(kGemmThreads, TB <= 2 ? 2 : 1) void gemm_stream_ker
       const int q = tid + i * kGemmThreads;
       const int r = q / (kSlabRowBytes / 16), cc = q % (kSlabRowBytes / 16);
       const int kk = k0 + cc * EPL;
-      xr[i] = *(const u32x4_t *)(xbase + ((size_t)(r < a.m ? r : 0) * a.ldx + (kk < k_end ? kk : k_begin)) * sizeof(T));
+      xr[i] = *(const u32x4_t *)(xbase + ((size_t)(r < a.m ? r : 0) * a.ldx + (kk < a.in ? kk : 0)) * sizeof(T));
     }
   };
   auto store_x = [&](int buf) {
@@ -155,7 +156,7 @@ __global__ __launch_bounds__(kGemmThreads, TB <= 2 ? 2 : 1) void gemm_stream_ker
 
   load_x(0);
 #define SPEC_LOADW(R, IT)                                                    \
-  { if ((IT) < n_full) load_w(ring[R], (IT)); else if ((IT) < n_iter) load_w_tail(ring[R], (IT)); }
+  { if ((IT) < n_iter) load_w(ring[R], (IT)); }
   SPEC_LOADW(0, 0)
   SPEC_LOADW(1, 1)
   store_x(0);
@@ -192,7 +193,7 @@ __global__ __launch_bounds__(kGemmThreads, TB <= 2 ? 2 : 1) void gemm_stream_ker
     if (more) store_x(buf ^ 1);                                              \
     __syncthreads();                                                         \
   }
-  const int n_steady = n_full >= 2 ? (n_full - 2) / 2 : 0;   // slabs S with 2S+3 < n_full (and so S+1 < n_slab)
+  const int n_steady = n_iter >= 2 ? (n_iter - 2) / 2 : 0;   // slabs S with 2S+3 < n_iter (and so S+1 < n_slab)
   int s = 0;
   for (; s + 3 <= n_steady; s += 3) {
     SPEC_FAST_SLAB(s, 0, 1, 2)        // iterations 6q+0, 6q+1 ; loads 6q+2 -> stage 2, 6q+3 -> stage 0
@@ -217,6 +218,43 @@ __global__ __launch_bounds__(kGemmThreads, TB <= 2 ? 2 : 1) void gemm_stream_ker
       const int i = t * 32 + 8 * (v >> 2) + 4 * g + (v & 3);
       if (i < a.m) out[(size_t)i * a.ldp] = acc[t][v];
     }
+}
+
+// ---- packing ---------------------------------------------------------------------------------
+// One thread moves one 16-byte piece: dst piece index p = ((rb * n_it + it) * 8 + j) * 64 + lane.
+template <typename T>
+__global__ __launch_bounds__(256) void pack_weight_kernel(const T *src, int rows, int in, u32x4_t *dst, size_t n_pieces) {
+  constexpr int EPL = GemmTraits<T>::kEpl;
+  constexpr int KI = 2 * kLaneBytes / (int)sizeof(T);
+  const int n_it = (in + KI - 1) / KI;
+  for (size_t p = (size_t)blockIdx.x * 256 + threadIdx.x; p < n_pieces; p += (size_t)gridDim.x * 256) {
+    const int lane = (int)(p & 63), j = (int)((p >> 6) & 7);
+    const size_t tile = p >> 9;
+    const int it = (int)(tile % n_it);
+    const int rb = (int)(tile / n_it);
+    const int row = rb * 32 + (lane & 31);
+    const int k = it * KI + (lane >> 5) * (KI / 2) + j * EPL;
+    u32x4_t v = {0u, 0u, 0u, 0u};
+    if (row < rows && k < in) v = *(const u32x4_t *)(src + (size_t)row * in + k);     // in % EPL == 0: whole piece in range
+    dst[p] = v;
+  }
+}
+
+size_t packed_weight_bytes(int dtype, int rows, int in) {
+  const int ki = gemm_k_per_iter(dtype);
+  return (size_t)((rows + 31) / 32) * (size_t)((in + ki - 1) / ki) * kTileBytes;
+}
+
+hipError_t launch_pack_weight(int dtype, const void *src, int rows, int in, void *dst, hipStream_t st) {
+  const int epl = dtype == 1 ? 8 : 4;
+  if (rows < 1 || in < 1 || in % epl) return hipErrorInvalidValue;
+  const size_t n_pieces = packed_weight_bytes(dtype, rows, in) / 16;
+  const int blocks = (int)std::min<size_t>((n_pieces + 255) / 256, 65536);
+  if (dtype == 1)
+    hipLaunchKernelGGL(pack_weight_kernel<bf16_t>, dim3(blocks), dim3(256), 0, st, (const bf16_t *)src, rows, in, (u32x4_t *)dst, n_pieces);
+  else
+    hipLaunchKernelGGL(pack_weight_kernel<float>, dim3(blocks), dim3(256), 0, st, (const float *)src, rows, in, (u32x4_t *)dst, n_pieces);
+  return hipGetLastError();
 }
 
 template <typename T>

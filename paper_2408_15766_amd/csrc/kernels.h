@@ -17,7 +17,7 @@ constexpr int kTopkSlice = 4096;       // vocabulary entries per first-stage top
 struct GemmArgs {
   const void *x;  int ldx;  int m;      // X [m, in], row stride ldx elements, 1 <= m <= 128
   int in;                               // K, a multiple of 16 bytes / element size
-  const void *seg_w[3];                 // up to three weight matrices [rows, in] sharing X (e.g. q, k, v)
+  const void *seg_w[3];                 // up to three PACKED weight matrices ([rows, in] before packing) sharing X (e.g. q, k, v)
   int seg_rows[3];
   int seg_blocks[3];                    // ceil(rows / 32)
   int seg_col0[3];                      // first output column of the segment
@@ -29,6 +29,9 @@ hipError_t launch_gemm(int dtype, const GemmArgs &a, hipStream_t st);
 int gemm_k_per_slab(int dtype);
 int gemm_k_per_iter(int dtype);
 int gemm_rows_per_group();
+// Packed layout of a row-major [rows, in] matrix (see gemm.hip): size in bytes, and the out-of-place repack.
+size_t packed_weight_bytes(int dtype, int rows, int in);
+hipError_t launch_pack_weight(int dtype, const void *src, int rows, int in, void *dst, hipStream_t st);
 
 // ---- rowops.hip ------------------------------------------------------------------------------
 // cos/sin of pos[i] * theta^(-2j/hd) for j < hd/2, angles formed in double precision.
@@ -66,9 +69,10 @@ struct AttnArgs {
   const int *depth;                     // [rows]
   const int *anc;                       // [rows][kAncStride] or nullptr
   float scale;
-  float *part;                          // scratch: [rows][hq][max_parts][hd + 2]
+  float *part;                          // scratch: [rows][hq][max_parts][hd + 2]; max_parts >= max_pos/256 + 2
   int max_parts;
   void *out;
+  int tail_only, bulk_blocks;           // set by launch_attention (hybrid matrix-core / vector split)
 };
 hipError_t launch_attention(int dtype, const AttnArgs &a, int max_pos, hipStream_t st);
 

@@ -32,45 +32,87 @@ hipError_t launch_rope_table(const int *pos, int rows, int head_dim, float theta
   return hipGetLastError();
 }
 
-// ---- shared tail: h_row already holds this thread's fp32 values (each thread re-reads only the
-// columns it wrote itself, so no barrier is needed for them); ss is the thread's sum of squares.
-template <typename T>
-__device__ __forceinline__ void finish_row(float ss, int d, const T *norm_w, float eps, const float *h_row, T *x_row,
-                                           float *sh) {
-  if (norm_w == nullptr) {
-    for (int c = threadIdx.x; c < d; c += kRowThreads) x_row[c] = from_f32<T>(h_row[c]);
-    return;
-  }
-  const float tot = block_sum(ss, sh);
-  const float r = 1.0f / sqrtf(tot / (float)d + eps);
-  for (int c = threadIdx.x; c < d; c += kRowThreads) x_row[c] = from_f32<T>(h_row[c] * r * to_f32(norm_w[c]));
+// ---- row kernels that end in an RMSNorm: one workgroup per row, the whole row held in registers ----
+// Thread t owns the 4-column groups t, t + 256, ... (PER of them, guarded), so all global loads of a
+// row are independent 16-byte loads issued up front, and the row is written exactly once.
+typedef __attribute__((ext_vector_type(4))) float f32x4_t;
+
+template <typename T> __device__ __forceinline__ f32x4_t load4(const T *p);
+template <> __device__ __forceinline__ f32x4_t load4<float>(const float *p) { return *(const f32x4_t *)p; }
+template <> __device__ __forceinline__ f32x4_t load4<bf16_t>(const bf16_t *p) {
+  const uint2 u = *(const uint2 *)p;
+  return f32x4_t{__uint_as_float(u.x << 16), __uint_as_float(u.x & 0xFFFF0000u), __uint_as_float(u.y << 16),
+                 __uint_as_float(u.y & 0xFFFF0000u)};
+}
+template <typename T> __device__ __forceinline__ void store4(T *p, f32x4_t v);
+template <> __device__ __forceinline__ void store4<float>(float *p, f32x4_t v) { *(f32x4_t *)p = v; }
+template <> __device__ __forceinline__ void store4<bf16_t>(bf16_t *p, f32x4_t v) {
+  uint2 u;
+  u.x = (uint32_t)f32_to_bf16_bits(v.x) | ((uint32_t)f32_to_bf16_bits(v.y) << 16);
+  u.y = (uint32_t)f32_to_bf16_bits(v.z) | ((uint32_t)f32_to_bf16_bits(v.w) << 16);
+  *(uint2 *)p = u;
 }
 
-template <typename T>
+template <typename T, int PER>
+__device__ __forceinline__ void finish_row(f32x4_t (&v)[PER], int d, const T *norm_w, float eps, float *h_row, T *x_row,
+                                           float *sh) {
+  float ss = 0.f;
+#pragma unroll
+  for (int e = 0; e < PER; e++) {
+    const int c = (e * kRowThreads + threadIdx.x) * 4;
+    if (c < d) {
+      *(f32x4_t *)(h_row + c) = v[e];
+      ss += v[e].x * v[e].x + v[e].y * v[e].y + v[e].z * v[e].z + v[e].w * v[e].w;
+    }
+  }
+  float r = 1.f;
+  if (norm_w != nullptr) r = 1.0f / sqrtf(block_sum(ss, sh) / (float)d + eps);
+#pragma unroll
+  for (int e = 0; e < PER; e++) {
+    const int c = (e * kRowThreads + threadIdx.x) * 4;
+    if (c < d) {
+      f32x4_t o = v[e];
+      if (norm_w != nullptr) o = o * r * load4<T>(norm_w + c);
+      store4<T>(x_row + c, o);
+    }
+  }
+}
+
+template <typename T, int PER>
 __global__ __launch_bounds__(kRowThreads) void embed_norm_kernel(const T *embed, const int *token, int d, const T *norm_w,
                                                                  float eps, float *h, T *x) {
   __shared__ float sh[16];
   const int i = blockIdx.x;
   const T *src = embed + (size_t)token[i] * d;
-  float *h_row = h + (size_t)i * d;
-  float ss = 0.f;
-  for (int c = threadIdx.x; c < d; c += kRowThreads) {
-    const float v = to_f32(src[c]);
-    h_row[c] = v;
-    ss += v * v;
+  f32x4_t v[PER];
+#pragma unroll
+  for (int e = 0; e < PER; e++) {
+    const int c = (e * kRowThreads + threadIdx.x) * 4;
+    v[e] = c < d ? load4<T>(src + c) : f32x4_t{0.f, 0.f, 0.f, 0.f};
   }
-  finish_row<T>(ss, d, norm_w, eps, h_row, x + (size_t)i * d, sh);
+  finish_row<T, PER>(v, d, norm_w, eps, h + (size_t)i * d, x + (size_t)i * d, sh);
+}
+
+template <typename T, int PER>
+static void embed_norm_launch(const void *embed, const int *token, int rows, int d, const void *norm_w, float eps, float *h,
+                              void *x, hipStream_t st) {
+  hipLaunchKernelGGL((embed_norm_kernel<T, PER>), dim3(rows), dim3(kRowThreads), 0, st, (const T *)embed, token, d,
+                     (const T *)norm_w, eps, h, (T *)x);
 }
 
 hipError_t launch_embed_norm(int dtype, const void *embed, const int *token, int rows, int d, const void *norm_w,
                              float eps, float *h, void *x, hipStream_t st) {
-  if (rows < 1 || d < 1) return hipErrorInvalidValue;
-  if (dtype == 1)
-    hipLaunchKernelGGL(embed_norm_kernel<bf16_t>, dim3(rows), dim3(kRowThreads), 0, st, (const bf16_t *)embed, token, d,
-                       (const bf16_t *)norm_w, eps, h, (bf16_t *)x);
-  else
-    hipLaunchKernelGGL(embed_norm_kernel<float>, dim3(rows), dim3(kRowThreads), 0, st, (const float *)embed, token, d,
-                       (const float *)norm_w, eps, h, (float *)x);
+  if (rows < 1 || d < 4 || d % 4 || d > kRowThreads * 4 * 16) return hipErrorInvalidValue;
+  const int per = (d + kRowThreads * 4 - 1) / (kRowThreads * 4);
+  if (dtype == 1) {
+    if (per <= 4) embed_norm_launch<bf16_t, 4>(embed, token, rows, d, norm_w, eps, h, x, st);
+    else if (per <= 8) embed_norm_launch<bf16_t, 8>(embed, token, rows, d, norm_w, eps, h, x, st);
+    else embed_norm_launch<bf16_t, 16>(embed, token, rows, d, norm_w, eps, h, x, st);
+  } else {
+    if (per <= 4) embed_norm_launch<float, 4>(embed, token, rows, d, norm_w, eps, h, x, st);
+    else if (per <= 8) embed_norm_launch<float, 8>(embed, token, rows, d, norm_w, eps, h, x, st);
+    else embed_norm_launch<float, 16>(embed, token, rows, d, norm_w, eps, h, x, st);
+  }
   return hipGetLastError();
 }
 
@@ -97,33 +139,46 @@ hipError_t launch_concat_feat_embed(int dtype, const void *feat, const int *src_
 }
 
 // ---- split sum (+ residual) + RMSNorm ------------------------------------------------------
-template <typename T>
+template <typename T, int PER>
 __global__ __launch_bounds__(kRowThreads) void reduce_add_norm_kernel(const float *part, int n_split, int m_pad, int ldp,
                                                                       int d, int residual, const T *norm_w, float eps,
                                                                       float *h, T *x) {
   __shared__ float sh[16];
   const int i = blockIdx.x;
   float *h_row = h + (size_t)i * d;
-  float ss = 0.f;
-  for (int c = threadIdx.x; c < d; c += kRowThreads) {
-    float acc = part[(size_t)i * ldp + c];
-    for (int s = 1; s < n_split; s++) acc += part[((size_t)s * m_pad + i) * ldp + c];   // fixed split order
-    const float v = residual ? h_row[c] + acc : acc;
-    h_row[c] = v;
-    ss += v * v;
+  f32x4_t v[PER];
+#pragma unroll
+  for (int e = 0; e < PER; e++) {
+    const int c = (e * kRowThreads + threadIdx.x) * 4;
+    f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
+    if (c < d) {
+      acc = *(const f32x4_t *)(part + (size_t)i * ldp + c);
+      for (int s = 1; s < n_split; s++) acc += *(const f32x4_t *)(part + ((size_t)s * m_pad + i) * ldp + c);   // fixed split order
+      if (residual) acc = *(const f32x4_t *)(h_row + c) + acc;
+    }
+    v[e] = acc;
   }
-  finish_row<T>(ss, d, norm_w, eps, h_row, x + (size_t)i * d, sh);
+  finish_row<T, PER>(v, d, norm_w, eps, h_row, x + (size_t)i * d, sh);
+}
+
+template <typename T, int PER>
+static void reduce_add_norm_launch(const float *part, int n_split, int m_pad, int ldp, int rows, int d, int residual,
+                                   const void *norm_w, float eps, float *h, void *x, hipStream_t st) {
+  hipLaunchKernelGGL((reduce_add_norm_kernel<T, PER>), dim3(rows), dim3(kRowThreads), 0, st, part, n_split, m_pad, ldp, d,
+                     residual, (const T *)norm_w, eps, h, (T *)x);
 }
 
 hipError_t launch_reduce_add_norm(int dtype, const float *part, int n_split, int m_pad, int ldp, int rows, int d,
                                   int residual, const void *norm_w, float eps, float *h, void *x, hipStream_t st) {
-  if (rows < 1 || d < 1) return hipErrorInvalidValue;
-  if (dtype == 1)
-    hipLaunchKernelGGL(reduce_add_norm_kernel<bf16_t>, dim3(rows), dim3(kRowThreads), 0, st, part, n_split, m_pad, ldp, d,
-                       residual, (const bf16_t *)norm_w, eps, h, (bf16_t *)x);
-  else
-    hipLaunchKernelGGL(reduce_add_norm_kernel<float>, dim3(rows), dim3(kRowThreads), 0, st, part, n_split, m_pad, ldp, d,
-                       residual, (const float *)norm_w, eps, h, (float *)x);
+  if (rows < 1 || d < 4 || d % 4 || ldp % 4 || d > kRowThreads * 4 * 16) return hipErrorInvalidValue;
+  const int per = (d + kRowThreads * 4 - 1) / (kRowThreads * 4);
+#define SPEC_RAN(T, P) reduce_add_norm_launch<T, P>(part, n_split, m_pad, ldp, rows, d, residual, norm_w, eps, h, x, st)
+  if (dtype == 1) {
+    if (per <= 4) SPEC_RAN(bf16_t, 4); else if (per <= 8) SPEC_RAN(bf16_t, 8); else SPEC_RAN(bf16_t, 16);
+  } else {
+    if (per <= 4) SPEC_RAN(float, 4); else if (per <= 8) SPEC_RAN(float, 8); else SPEC_RAN(float, 16);
+  }
+#undef SPEC_RAN
   return hipGetLastError();
 }
 
