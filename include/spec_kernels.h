@@ -35,7 +35,7 @@ int spec_k_gemm(int32_t dtype, const void *x, int32_t ldx, int32_t m, int32_t in
  * positions 0 .. base + depth[i]: position p < base is cache row p, position
  * p >= base is cache row base + anc[i*16 + p - base] (anc NULL: row p).
  * kcache, vcache: [*, hkv*hd].  out: [rows, hq*hd] in dtype.  scratch: fp32,
- * rows*hq*max_parts*(hd+2) floats with max_parts >= (base+max depth)/256 + 2.
+ * rows*hq*max_parts*(hd+2) floats with max_parts >= (base+max depth)/128 + 2.
  * hd must be 64 or 128, hq/hkv one of 1, 2, 4, 8. */
 int spec_k_attention(int32_t dtype, const void *q, const void *kcache, const void *vcache, int32_t rows, int32_t hq,
                      int32_t hkv, int32_t hd, int32_t base, const int32_t *depth, const int32_t *anc, int32_t max_depth,

@@ -251,7 +251,7 @@ def spec_k_attention(q, kcache, vcache, base: int, depth, anc, hq: int, hkv: int
     dtype = 1 if kcache.dtype == torch.bfloat16 else 0
     rows = q.shape[0]
     max_depth = int(depth.max().item())
-    max_parts = (base + max_depth) // 256 + 2
+    max_parts = (base + max_depth) // 128 + 2
     scratch = torch.empty(rows * hq * max_parts * (hd + 2), dtype=torch.float32, device=q.device)
     out = torch.empty(q.shape, dtype=kcache.dtype, device=q.device)
     rc = lib.spec_k_attention(dtype, q.data_ptr(), kcache.data_ptr(), vcache.data_ptr(), rows, hq, hkv, hd, base,

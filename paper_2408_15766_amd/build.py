@@ -16,26 +16,27 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Xclang", "-tar
          "-I" + os.path.join(os.path.dirname(HERE), "include")]
 
 
-def _compile(src: str, objdir: str) -> str:
+def _compile(src: str, objdir: str, extra=()) -> str:
     obj = os.path.join(objdir, src + ".o")
-    cmd = [HIPCC] + FLAGS + ["-c", os.path.join(CSRC, src), "-o", obj]
+    cmd = [HIPCC] + FLAGS + list(extra) + ["-c", os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError(f"hipcc failed for {src}:\n{r.stderr}")
     return obj
 
 
-def build(verbose: bool = True) -> str:
-    objdir = os.path.join(HERE, "_build")
+def build(verbose: bool = True, extra_flags=(), out: str = LIB, tag: str = "") -> str:
+    """Compile and link.  extra_flags / out / tag build a tuning variant next to the product library."""
+    objdir = os.path.join(HERE, "_build" + tag)
     os.makedirs(objdir, exist_ok=True)
     with ThreadPoolExecutor(max_workers=min(5, os.cpu_count() or 1)) as ex:
-        objs = list(ex.map(lambda s: _compile(s, objdir), SOURCES))
-    r = subprocess.run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + objs, capture_output=True, text=True)
+        objs = list(ex.map(lambda s: _compile(s, objdir, extra_flags), SOURCES))
+    r = subprocess.run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", out] + objs, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError(f"link failed:\n{r.stderr}")
     if verbose:
-        print(f"built {LIB}", file=sys.stderr)
-    return LIB
+        print(f"built {out}", file=sys.stderr)
+    return out
 
 
 if __name__ == "__main__":

@@ -118,8 +118,12 @@ GemmPlan plan_gemm(int total_rows, int in, int dtype) {
   const int groups = (blocks + gemm_rows_per_group() / 32 - 1) / (gemm_rows_per_group() / 32);
   const int kslab = gemm_k_per_slab(dtype);
   const int slabs = (in + kslab - 1) / kslab;
-  int s = std::max(1, std::min(8, 512 / std::max(1, groups)));   // aim at ~2 workgroups per CU
-  s = std::min(s, std::max(1, slabs / 4));                        // but keep >= 4 slabs per split
+  // Measured on MI355X: streaming is fastest with the fewest K splits that still put a workgroup on
+  // most of the 256 CUs (each extra split adds a partial-sum round trip and shortens the streams);
+  // power-of-two counts keep the K ranges even.
+  int s = 1;
+  while (groups * s < 160 && s < 8) s *= 2;
+  while (s > 1 && slabs / s < 4) s /= 2;                          // keep >= 4 slabs per split
   GemmPlan p;
   p.n_split = s;
   return p;

@@ -11,10 +11,11 @@
 //
 // Two code paths share one definition of the key order:
 //
-//  * vector path (attn_part_kernel): one wavefront handles (row, kv head, part of kAttnPart = 256
+//  * vector path (attn_part_kernel): one wavefront handles (row, kv head, part of kAttnPart = 128
 //    key positions) and all G query heads that share the kv head; keys are taken 64 at a time,
-//    lane = position offset, wave shuffles give the running max and sum of the online softmax,
-//    P*V is accumulated key by key in position order.  Used for fp32 storage, and for the TAIL
+//    lane = position offset for the scores (wave shuffles give the running max and sum of the
+//    online softmax), then lane = output dim for P*V, which runs over the value rows staged in
+//    LDS key by key in position order.  Used for fp32 storage, and for the TAIL
 //    of every row in bf16 storage.
 //
 //  * matrix-core path (attn_bulk_kernel, bf16 storage): the BULK of a row's keys, positions
@@ -60,8 +61,10 @@ __device__ __host__ __forceinline__ int bulk_end(int p) { return p > kMaxDepth ?
 template <typename T, int HD, int G>
 __global__ __launch_bounds__(64) void attn_part_kernel(AttnArgs a) {
   constexpr int EPL = Chunk<T>::kEpl;
-  constexpr int DPL = HD / 64;                       // output dims per lane
+  constexpr int DPL = HD / 64;                       // output dims per lane (contiguous)
+  constexpr int VROW = HD * (int)sizeof(T) + 16;     // LDS bytes per staged value row (+16: conflict-free row writes)
   __shared__ __attribute__((aligned(16))) float qs[G][HD];
+  __shared__ __attribute__((aligned(16))) unsigned char vs[64 * VROW];
   const int i = blockIdx.x, hk = blockIdx.y, part = blockIdx.z, lane = threadIdx.x;
   const int p = a.base + a.depth[i];
   // full mode: part `part` of the whole range [0, p]; tail mode: the single range [A(p), p]
@@ -72,7 +75,6 @@ __global__ __launch_bounds__(64) void attn_part_kernel(AttnArgs a) {
 
   const float *qrow = (const float *)a.q + ((size_t)i * a.hq + (size_t)hk * G) * HD;   // queries are fp32
   for (int e = lane; e < G * HD; e += 64) qs[e / HD][e % HD] = qrow[e];
-  __syncthreads();
 
   float m_run[G], l_run[G], o[G][DPL];
 #pragma unroll
@@ -84,52 +86,69 @@ __global__ __launch_bounds__(64) void attn_part_kernel(AttnArgs a) {
   const int *anc = a.anc ? a.anc + (size_t)i * kAncStride : nullptr;
   const size_t row_stride = (size_t)a.hkv * HD;
   const T *kbase = (const T *)a.kcache + (size_t)hk * HD;
-  const T *vbase = (const T *)a.vcache + (size_t)hk * HD + lane * DPL;
+  const T *vbase = (const T *)a.vcache + (size_t)hk * HD;
 
   for (int kb = k_lo; kb < k_hi; kb += 64) {
+    // lane = key: this lane's key row and value row (all loads issued before anything is used)
     const int kq = kb + lane;
     const bool valid = kq < k_hi;
     int slot = 0;
     if (valid) slot = kq < a.base ? kq : a.base + (anc ? anc[kq - a.base] : kq - a.base);
     const T *kptr = kbase + (size_t)slot * row_stride;
+    const T *vptr = vbase + (size_t)slot * row_stride;
+    u32x4_t kc[HD / EPL], vc[HD / EPL];
+#pragma unroll
+    for (int dc = 0; dc < HD / EPL; dc++) kc[dc] = *(const u32x4_t *)(kptr + dc * EPL);
+#pragma unroll
+    for (int dc = 0; dc < HD / EPL; dc++) vc[dc] = *(const u32x4_t *)(vptr + dc * EPL);
+    __syncthreads();                                   // qs written (first pass) / previous block's vs reads done
     float s[G];
 #pragma unroll
     for (int gh = 0; gh < G; gh++) s[gh] = 0.f;
-#pragma unroll 4
+#pragma unroll
     for (int dc = 0; dc < HD / EPL; dc++) {
-      const u32x4_t ck = *(const u32x4_t *)(kptr + dc * EPL);
       float kf[EPL];
-      Chunk<T>::unpack(ck, kf);
+      Chunk<T>::unpack(kc[dc], kf);
 #pragma unroll
       for (int gh = 0; gh < G; gh++)
 #pragma unroll
         for (int e = 0; e < EPL; e++) s[gh] = fmaf(qs[gh][dc * EPL + e], kf[e], s[gh]);
     }
+    // stage the value rows: row `lane` of vs
+#pragma unroll
+    for (int dc = 0; dc < HD / EPL; dc++) *(u32x4_t *)(vs + lane * VROW + dc * 16) = vc[dc];
     float pk[G];
 #pragma unroll
     for (int gh = 0; gh < G; gh++) {
       const float sc = valid ? s[gh] * a.scale : -INFINITY;
       const float m_new = fmaxf(m_run[gh], wave_max(sc));
-      const float corr = expf(m_run[gh] - m_new);        // first block: exp(-inf) = 0
-      pk[gh] = valid ? expf(sc - m_new) : 0.f;
+      const float corr = __expf(m_run[gh] - m_new);      // first block: exp(-inf) = 0
+      pk[gh] = valid ? __expf(sc - m_new) : 0.f;
       l_run[gh] = l_run[gh] * corr + wave_sum(pk[gh]);
 #pragma unroll
       for (int dd = 0; dd < DPL; dd++) o[gh][dd] *= corr;
       m_run[gh] = m_new;
     }
+    __syncthreads();                                   // value rows staged
+    // lane = output dims lane*DPL ..: accumulate key by key in position order
+    // Eight keys per step so that the LDS reads of a step are in flight together.  Lanes past the last
+    // key hold weight 0 and a valid finite value row (slot 0), so rounding a step up to eight adds zeros.
     const int nk = min(64, k_hi - kb);
-    for (int k = 0; k < nk; k++) {
-      const int sl = __shfl(slot, k, 64);
-      const T *vp = vbase + (size_t)sl * row_stride;
-      float vv[DPL];
+    const unsigned char *vcol = vs + lane * DPL * (int)sizeof(T);
+    for (int k0 = 0; k0 < nk; k0 += 8) {
+      float vv[8][DPL];
 #pragma unroll
-      for (int dd = 0; dd < DPL; dd++) vv[dd] = to_f32(vp[dd]);
+      for (int kk = 0; kk < 8; kk++)
 #pragma unroll
-      for (int gh = 0; gh < G; gh++) {
-        const float w = __shfl(pk[gh], k, 64);
+        for (int dd = 0; dd < DPL; dd++) vv[kk][dd] = to_f32(*(const T *)(vcol + (k0 + kk) * VROW + dd * (int)sizeof(T)));
 #pragma unroll
-        for (int dd = 0; dd < DPL; dd++) o[gh][dd] = fmaf(w, vv[dd], o[gh][dd]);
-      }
+      for (int kk = 0; kk < 8; kk++)
+#pragma unroll
+        for (int gh = 0; gh < G; gh++) {
+          const float w = __shfl(pk[gh], k0 + kk, 64);
+#pragma unroll
+          for (int dd = 0; dd < DPL; dd++) o[gh][dd] = fmaf(w, vv[kk][dd], o[gh][dd]);
+        }
     }
   }
 #pragma unroll
@@ -146,7 +165,7 @@ template <typename T, int HD>
 __global__ void attn_combine_kernel(AttnArgs a) {
   const int i = blockIdx.x, h = blockIdx.y, d = threadIdx.x;
   const int p = a.base + a.depth[i];
-  // full mode: parts 0 .. p/256; hybrid mode: the bulk parts that hold keys of this row, then the tail slot
+  // full mode: parts 0 .. p/kAttnPart; hybrid mode: the bulk parts that hold keys of this row, then the tail slot
   const int n_parts = a.tail_only ? (bulk_end(p) + kAttnPart - 1) / kAttnPart : p / kAttnPart + 1;
   const float *src = a.part + ((size_t)i * a.hq + h) * a.max_parts * (HD + 2);
   const float *tail = src + (size_t)(a.max_parts - 1) * (HD + 2);
@@ -155,12 +174,12 @@ __global__ void attn_combine_kernel(AttnArgs a) {
   float l = 0.f, o = 0.f;
   for (int t = 0; t < n_parts; t++) {
     const float *s = src + (size_t)t * (HD + 2);
-    const float w = expf(s[0] - m);
+    const float w = __expf(s[0] - m);
     l += s[1] * w;
     o += s[2 + d] * w;
   }
   if (a.tail_only) {
-    const float w = expf(tail[0] - m);
+    const float w = __expf(tail[0] - m);
     l += tail[1] * w;
     o += tail[2 + d] * w;
   }
@@ -173,16 +192,15 @@ typedef __attribute__((ext_vector_type(16))) float f32x16_t;
 typedef __attribute__((ext_vector_type(2))) uint32_t u32x2_t;
 
 // x = hi + lo with hi, lo bf16: the pair keeps ~16 mantissa bits of an fp32 value.
-__device__ __forceinline__ void split_bf16(float x, uint32_t &hi, uint32_t &lo) {
-  hi = f32_to_bf16_bits(x);
-  lo = f32_to_bf16_bits(x - bf16_bits_to_f32(hi));
-}
 __device__ __forceinline__ void split8(const float (&x)[8], u32x4_t &hi, u32x4_t &lo) {
-  uint32_t h[8], l[8];
+  uint32_t h[4], l[4];
 #pragma unroll
-  for (int e = 0; e < 8; e++) split_bf16(x[e], h[e], l[e]);
-  hi = u32x4_t{h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16)};
-  lo = u32x4_t{l[0] | (l[1] << 16), l[2] | (l[3] << 16), l[4] | (l[5] << 16), l[6] | (l[7] << 16)};
+  for (int e = 0; e < 4; e++) {
+    h[e] = pack_bf16x2(x[2 * e], x[2 * e + 1]);
+    l[e] = pack_bf16x2(x[2 * e] - __uint_as_float(h[e] << 16), x[2 * e + 1] - __uint_as_float(h[e] & 0xFFFF0000u));
+  }
+  hi = u32x4_t{h[0], h[1], h[2], h[3]};
+  lo = u32x4_t{l[0], l[1], l[2], l[3]};
 }
 __device__ __forceinline__ f32x16_t mfma_bf16(const u32x4_t &a, const u32x4_t &b, f32x16_t c) {
   return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, a), __builtin_bit_cast(bf16x8_t, b), c, 0, 0, 0);
@@ -286,10 +304,10 @@ __global__ __launch_bounds__(NW * 64) void attn_bulk_kernel(AttnArgs a) {
     for (int v = 0; v < 16; v++) { s[v] = incl ? s[v] * a.scale : -INFINITY; mb = fmaxf(mb, s[v]); }
     mb = fmaxf(mb, __shfl_xor(mb, 32, 64));
     const float m_new = fmaxf(m_run, mb);
-    const float corr = m_new == -INFINITY ? 1.f : expf(m_run - m_new);
+    const float corr = m_new == -INFINITY ? 1.f : __expf(m_run - m_new);
     float pv[16], ls = 0.f;
 #pragma unroll
-    for (int v = 0; v < 16; v++) { pv[v] = incl ? expf(s[v] - m_new) : 0.f; ls += pv[v]; }
+    for (int v = 0; v < 16; v++) { pv[v] = incl ? __expf(s[v] - m_new) : 0.f; ls += pv[v]; }
     ls += __shfl_xor(ls, 32, 64);
     l_run = l_run * corr + ls;
     m_run = m_new;

@@ -12,10 +12,14 @@ constexpr int kWave = 64;
 struct bf16_t { uint16_t v; };
 
 __device__ __forceinline__ float bf16_bits_to_f32(uint32_t b) { return __uint_as_float(b << 16); }
-__device__ __forceinline__ uint16_t f32_to_bf16_bits(float f) {   // round to nearest, ties to even
-  uint32_t u = __float_as_uint(f);
-  u += 0x7FFFu + ((u >> 16) & 1u);
-  return (uint16_t)(u >> 16);
+__device__ __forceinline__ uint16_t f32_to_bf16_bits(float f) {   // round to nearest, ties to even (v_cvt_pk_bf16_f32)
+  return __builtin_bit_cast(uint16_t, (__bf16)f);
+}
+// two floats -> two bf16 in one dword (lo in the low half), one hardware conversion
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+  typedef __attribute__((ext_vector_type(2))) float f2_t;
+  typedef __attribute__((ext_vector_type(2))) __bf16 b2_t;
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(f2_t{lo, hi}, b2_t));
 }
 __device__ __forceinline__ float to_f32(float x) { return x; }
 __device__ __forceinline__ float to_f32(bf16_t x) { return bf16_bits_to_f32(x.v); }

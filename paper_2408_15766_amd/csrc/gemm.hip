@@ -35,6 +35,7 @@
 // other rows, so a token computes bit-identical results alone (plain decoding)
 // or inside a tree.
 #include <algorithm>
+#include <type_traits>
 
 #include "common.h"
 #include "kernels.h"
@@ -45,10 +46,16 @@ typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
 typedef __attribute__((ext_vector_type(16))) float f32x16_t;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;   // native vector: stays in registers (SSA), unlike HIP's u32x4_t struct
 
-constexpr int kGemmWaves = 4;                       // waves per workgroup
+#ifndef SPEC_GEMM_WAVES
+#define SPEC_GEMM_WAVES 4
+#endif
+#ifndef SPEC_GEMM_SLAB_ITERS
+#define SPEC_GEMM_SLAB_ITERS 2
+#endif
+constexpr int kGemmWaves = SPEC_GEMM_WAVES;         // waves per workgroup
 constexpr int kGemmThreads = kGemmWaves * kWave;
 constexpr int kLaneBytes = 128;                     // contiguous weight bytes per lane per iteration
-constexpr int kSlabIters = 2;                       // iterations per LDS slab
+constexpr int kSlabIters = SPEC_GEMM_SLAB_ITERS;    // iterations per LDS slab
 constexpr int kSlabRowBytes = 2 * kLaneBytes * kSlabIters;   // 512 B of k per token row per slab
 constexpr int kSlabStride = kSlabRowBytes + 16;     // +16 B: conflict-free 16-byte LDS reads
 constexpr int kTileBytes = 32 * 2 * kLaneBytes;     // one packed tile: 32 rows x 256 B of k
@@ -121,7 +128,7 @@ __global__ __launch_bounds__(kGemmThreads, TB <= 2 ? 2 : 1) void gemm_stream_ker
   auto load_w = [&](u32x4_t (&dst)[8], int it) {
     const char *p = wstream + (size_t)it * kTileBytes;
 #pragma unroll
-    for (int j = 0; j < 8; j++) dst[j] = *(const u32x4_t *)(p + j * 1024);
+    for (int j = 0; j < 8; j++) dst[j] = __builtin_nontemporal_load((const u32x4_t *)(p + j * 1024));   // read once: do not keep in cache
   };
   const char *xbase = (const char *)a.x;
   auto load_x = [&](int slab) {
@@ -155,59 +162,51 @@ __global__ __launch_bounds__(kGemmThreads, TB <= 2 ? 2 : 1) void gemm_stream_ker
   };
 
   load_x(0);
-#define SPEC_LOADW(R, IT)                                                    \
-  { if ((IT) < n_iter) load_w(ring[R], (IT)); }
-  SPEC_LOADW(0, 0)
-  SPEC_LOADW(1, 1)
+  if (0 < n_iter) load_w(ring[0], 0);
+  if (1 < n_iter) load_w(ring[1], 1);
   store_x(0);
   __syncthreads();
 
-  // One slab = kSlabIters (2) iterations; the ring stage of iteration `it` is it % 3, so three
-  // slabs (six iterations) form one period and are unrolled to keep register indices static.
-  // Steady state: every load of the slab is a full, in-range iteration and a next slab exists,
-  // so the body has no branch and the compiler can keep exact outstanding-load counts.
-#define SPEC_FAST_SLAB(S, R0, R1, R2)                                        \
-  {                                                                          \
-    const int buf = (S) & 1;                                                 \
-    load_x((S) + 1);                                                         \
-    load_w(ring[R2], (S) * 2 + 2);                                           \
-    __builtin_amdgcn_sched_barrier(0); /* keep the prefetches ahead of the MFMAs */ \
-    compute(ring[R0], buf, 0);                                               \
-    __builtin_amdgcn_sched_barrier(0);                                       \
-    load_w(ring[R0], (S) * 2 + 3);                                           \
-    __builtin_amdgcn_sched_barrier(0);                                       \
-    compute(ring[R1], buf, 1);                                               \
-    __builtin_amdgcn_sched_barrier(0);                                       \
-    store_x(buf ^ 1);                                                        \
-    __syncthreads();                                                         \
-  }
-#define SPEC_SLAB(S, R0, R1, R2)                                             \
-  if ((S) < n_slab) {                                                        \
-    const int buf = (S) & 1;                                                 \
-    const bool more = (S) + 1 < n_slab;                                      \
-    if (more) load_x((S) + 1);                                               \
-    SPEC_LOADW(R2, (S) * 2 + 2)                                              \
-    compute(ring[R0], buf, 0);                                               \
-    SPEC_LOADW(R0, (S) * 2 + 3)                                              \
-    if ((S) * 2 + 1 < n_iter) compute(ring[R1], buf, 1);                     \
-    if (more) store_x(buf ^ 1);                                              \
-    __syncthreads();                                                         \
-  }
-  const int n_steady = n_iter >= 2 ? (n_iter - 2) / 2 : 0;   // slabs S with 2S+3 < n_iter (and so S+1 < n_slab)
+  // The ring stage of iteration `it` is it % 3.  A slab is kSlabIters iterations, so three slabs
+  // form one period of the stage pattern and are unrolled with compile-time stage indices
+  // (P = slab index mod 3).  Steady state (FAST): every load of the slab is a full, in-range
+  // iteration and a next slab exists, so the body has no branch and the compiler keeps exact
+  // outstanding-load counts; the remaining slabs take the guarded form.
+  auto slab = [&](auto p_tag, auto fast_tag, int S) {
+    constexpr int P = decltype(p_tag)::value;
+    constexpr bool FAST = decltype(fast_tag)::value;
+    if (!FAST && S >= n_slab) return;
+    const int buf = S & 1;
+    const bool more = FAST || S + 1 < n_slab;
+    if (more) load_x(S + 1);
+#pragma unroll
+    for (int ii = 0; ii < kSlabIters; ii++) {
+      constexpr int base_stage = (kSlabIters * P) % 3;
+      const int it = S * kSlabIters + ii;
+      // stage indices are compile-time after unrolling: (base_stage + ii) % 3 etc.
+      const int st_use = (base_stage + ii) % 3, st_load = (base_stage + ii + 2) % 3;
+      if (FAST || it + 2 < n_iter) load_w(ring[st_load], it + 2);
+      __builtin_amdgcn_sched_barrier(0);                     // keep the prefetch ahead of the MFMAs
+      if (FAST || it < n_iter) compute(ring[st_use], buf, ii);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    if (more) store_x(buf ^ 1);
+    __syncthreads();
+  };
+  using I0 = std::integral_constant<int, 0>; using I1 = std::integral_constant<int, 1>; using I2 = std::integral_constant<int, 2>;
+  // slabs S for which iteration S*kSlabIters + kSlabIters + 1 (the last one loaded) is in range
+  const int n_steady = n_iter >= kSlabIters + 2 ? (n_iter - 2) / kSlabIters : 0;
   int s = 0;
   for (; s + 3 <= n_steady; s += 3) {
-    SPEC_FAST_SLAB(s, 0, 1, 2)        // iterations 6q+0, 6q+1 ; loads 6q+2 -> stage 2, 6q+3 -> stage 0
-    SPEC_FAST_SLAB(s + 1, 2, 0, 1)    // iterations 6q+2, 6q+3 ; loads 6q+4 -> stage 1, 6q+5 -> stage 2
-    SPEC_FAST_SLAB(s + 2, 1, 2, 0)    // iterations 6q+4, 6q+5 ; loads 6q+6 -> stage 0, 6q+7 -> stage 1
+    slab(I0{}, std::true_type{}, s);
+    slab(I1{}, std::true_type{}, s + 1);
+    slab(I2{}, std::true_type{}, s + 2);
   }
   for (; s < n_slab; s += 3) {
-    SPEC_SLAB(s, 0, 1, 2)
-    SPEC_SLAB(s + 1, 2, 0, 1)
-    SPEC_SLAB(s + 2, 1, 2, 0)
+    slab(I0{}, std::false_type{}, s);
+    slab(I1{}, std::false_type{}, s + 1);
+    slab(I2{}, std::false_type{}, s + 2);
   }
-#undef SPEC_SLAB
-#undef SPEC_FAST_SLAB
-#undef SPEC_LOADW
 
   if (!active || row >= seg_rows) return;
   float *out = a.part + ((size_t)blockIdx.y * a.m_pad) * a.ldp + seg_col0 + row;
@@ -263,15 +262,14 @@ static hipError_t launch_t(const GemmArgs &a, hipStream_t st) {
   dim3 grid((a.total_blocks + kGemmWaves - 1) / kGemmWaves, a.n_split);
   const size_t lds = (size_t)2 * tb * 32 * kSlabStride;
   // the double-buffered slab exceeds the 64 KiB default for dynamic LDS from two token blocks on
-  static bool attr_set = false;
-  if (!attr_set) {
-    const int big = 4 * 2 * 32 * kSlabStride;
-    hipError_t e = hipFuncSetAttribute((const void *)gemm_stream_kernel<T, 1>, hipFuncAttributeMaxDynamicSharedMemorySize, big);
-    if (e == hipSuccess) e = hipFuncSetAttribute((const void *)gemm_stream_kernel<T, 2>, hipFuncAttributeMaxDynamicSharedMemorySize, big);
-    if (e == hipSuccess) e = hipFuncSetAttribute((const void *)gemm_stream_kernel<T, 3>, hipFuncAttributeMaxDynamicSharedMemorySize, big);
-    if (e == hipSuccess) e = hipFuncSetAttribute((const void *)gemm_stream_kernel<T, 4>, hipFuncAttributeMaxDynamicSharedMemorySize, big);
+  static bool attr_set[5] = {false, false, false, false, false};
+  if (lds > 160 * 1024) return hipErrorInvalidValue;
+  if (!attr_set[tb]) {
+    const void *fn = tb == 1 ? (const void *)gemm_stream_kernel<T, 1> : tb == 2 ? (const void *)gemm_stream_kernel<T, 2>
+                   : tb == 3 ? (const void *)gemm_stream_kernel<T, 3> : (const void *)gemm_stream_kernel<T, 4>;
+    hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
-    attr_set = true;
+    attr_set[tb] = true;
   }
   switch (tb) {
     case 1: hipLaunchKernelGGL((gemm_stream_kernel<T, 1>), grid, dim3(kGemmThreads), lds, st, a); break;

@@ -10,7 +10,7 @@ constexpr int kMaxDepth = 15;          // longest root-to-node path handled by t
 constexpr int kAncStride = kMaxDepth + 1;
 constexpr int kMaxTopK = 16;
 constexpr int kMaxNodes = 128;
-constexpr int kAttnPart = 256;         // key positions per attention partial (fixed absolute boundaries)
+constexpr int kAttnPart = 128;         // key positions per attention partial (fixed absolute boundaries)
 constexpr int kTopkSlice = 4096;       // vocabulary entries per first-stage top-k workgroup
 
 // ---- gemm.hip --------------------------------------------------------------------------------
@@ -69,7 +69,7 @@ struct AttnArgs {
   const int *depth;                     // [rows]
   const int *anc;                       // [rows][kAncStride] or nullptr
   float scale;
-  float *part;                          // scratch: [rows][hq][max_parts][hd + 2]; max_parts >= max_pos/256 + 2
+  float *part;                          // scratch: [rows][hq][max_parts][hd + 2]; max_parts >= max_pos/kAttnPart + 2
   int max_parts;
   void *out;
   int tail_only, bulk_blocks;           // set by launch_attention (hybrid matrix-core / vector split)

@@ -11,7 +11,8 @@
 
 namespace spec {
 
-constexpr int kRowThreads = 256;
+constexpr int kRowThreads = 256;      // threads of the elementwise kernels
+constexpr int kNormThreads = 1024;    // threads of the kernels that hold one row per workgroup
 
 // ---- rotary table ------------------------------------------------------------------------
 __global__ void rope_table_kernel(const int *pos, int rows, int half, double log2_theta, float2 *table) {
@@ -33,8 +34,9 @@ hipError_t launch_rope_table(const int *pos, int rows, int head_dim, float theta
 }
 
 // ---- row kernels that end in an RMSNorm: one workgroup per row, the whole row held in registers ----
-// Thread t owns the 4-column groups t, t + 256, ... (PER of them, guarded), so all global loads of a
-// row are independent 16-byte loads issued up front, and the row is written exactly once.
+// Thread t owns the 4-column groups t, t + 1024, ... (PER of them, guarded), so all global loads of a
+// row are independent 16-byte loads issued up front, and the row is written exactly once.  With 1024
+// threads a 4096-wide row is one group per thread: the kernel is three dependent memory round trips.
 typedef __attribute__((ext_vector_type(4))) float f32x4_t;
 
 template <typename T> __device__ __forceinline__ f32x4_t load4(const T *p);
@@ -59,7 +61,7 @@ __device__ __forceinline__ void finish_row(f32x4_t (&v)[PER], int d, const T *no
   float ss = 0.f;
 #pragma unroll
   for (int e = 0; e < PER; e++) {
-    const int c = (e * kRowThreads + threadIdx.x) * 4;
+    const int c = (e * kNormThreads + threadIdx.x) * 4;
     if (c < d) {
       *(f32x4_t *)(h_row + c) = v[e];
       ss += v[e].x * v[e].x + v[e].y * v[e].y + v[e].z * v[e].z + v[e].w * v[e].w;
@@ -69,7 +71,7 @@ __device__ __forceinline__ void finish_row(f32x4_t (&v)[PER], int d, const T *no
   if (norm_w != nullptr) r = 1.0f / sqrtf(block_sum(ss, sh) / (float)d + eps);
 #pragma unroll
   for (int e = 0; e < PER; e++) {
-    const int c = (e * kRowThreads + threadIdx.x) * 4;
+    const int c = (e * kNormThreads + threadIdx.x) * 4;
     if (c < d) {
       f32x4_t o = v[e];
       if (norm_w != nullptr) o = o * r * load4<T>(norm_w + c);
@@ -79,7 +81,7 @@ __device__ __forceinline__ void finish_row(f32x4_t (&v)[PER], int d, const T *no
 }
 
 template <typename T, int PER>
-__global__ __launch_bounds__(kRowThreads) void embed_norm_kernel(const T *embed, const int *token, int d, const T *norm_w,
+__global__ __launch_bounds__(kNormThreads) void embed_norm_kernel(const T *embed, const int *token, int d, const T *norm_w,
                                                                  float eps, float *h, T *x) {
   __shared__ float sh[16];
   const int i = blockIdx.x;
@@ -87,7 +89,7 @@ __global__ __launch_bounds__(kRowThreads) void embed_norm_kernel(const T *embed,
   f32x4_t v[PER];
 #pragma unroll
   for (int e = 0; e < PER; e++) {
-    const int c = (e * kRowThreads + threadIdx.x) * 4;
+    const int c = (e * kNormThreads + threadIdx.x) * 4;
     v[e] = c < d ? load4<T>(src + c) : f32x4_t{0.f, 0.f, 0.f, 0.f};
   }
   finish_row<T, PER>(v, d, norm_w, eps, h + (size_t)i * d, x + (size_t)i * d, sh);
@@ -96,22 +98,22 @@ __global__ __launch_bounds__(kRowThreads) void embed_norm_kernel(const T *embed,
 template <typename T, int PER>
 static void embed_norm_launch(const void *embed, const int *token, int rows, int d, const void *norm_w, float eps, float *h,
                               void *x, hipStream_t st) {
-  hipLaunchKernelGGL((embed_norm_kernel<T, PER>), dim3(rows), dim3(kRowThreads), 0, st, (const T *)embed, token, d,
+  hipLaunchKernelGGL((embed_norm_kernel<T, PER>), dim3(rows), dim3(kNormThreads), 0, st, (const T *)embed, token, d,
                      (const T *)norm_w, eps, h, (T *)x);
 }
 
 hipError_t launch_embed_norm(int dtype, const void *embed, const int *token, int rows, int d, const void *norm_w,
                              float eps, float *h, void *x, hipStream_t st) {
-  if (rows < 1 || d < 4 || d % 4 || d > kRowThreads * 4 * 16) return hipErrorInvalidValue;
-  const int per = (d + kRowThreads * 4 - 1) / (kRowThreads * 4);
+  if (rows < 1 || d < 4 || d % 4 || d > kNormThreads * 4 * 4) return hipErrorInvalidValue;
+  const int per = (d + kNormThreads * 4 - 1) / (kNormThreads * 4);
   if (dtype == 1) {
-    if (per <= 4) embed_norm_launch<bf16_t, 4>(embed, token, rows, d, norm_w, eps, h, x, st);
-    else if (per <= 8) embed_norm_launch<bf16_t, 8>(embed, token, rows, d, norm_w, eps, h, x, st);
-    else embed_norm_launch<bf16_t, 16>(embed, token, rows, d, norm_w, eps, h, x, st);
+    if (per <= 1) embed_norm_launch<bf16_t, 1>(embed, token, rows, d, norm_w, eps, h, x, st);
+    else if (per <= 2) embed_norm_launch<bf16_t, 2>(embed, token, rows, d, norm_w, eps, h, x, st);
+    else embed_norm_launch<bf16_t, 4>(embed, token, rows, d, norm_w, eps, h, x, st);
   } else {
-    if (per <= 4) embed_norm_launch<float, 4>(embed, token, rows, d, norm_w, eps, h, x, st);
-    else if (per <= 8) embed_norm_launch<float, 8>(embed, token, rows, d, norm_w, eps, h, x, st);
-    else embed_norm_launch<float, 16>(embed, token, rows, d, norm_w, eps, h, x, st);
+    if (per <= 1) embed_norm_launch<float, 1>(embed, token, rows, d, norm_w, eps, h, x, st);
+    else if (per <= 2) embed_norm_launch<float, 2>(embed, token, rows, d, norm_w, eps, h, x, st);
+    else embed_norm_launch<float, 4>(embed, token, rows, d, norm_w, eps, h, x, st);
   }
   return hipGetLastError();
 }
@@ -140,7 +142,7 @@ hipError_t launch_concat_feat_embed(int dtype, const void *feat, const int *src_
 
 // ---- split sum (+ residual) + RMSNorm ------------------------------------------------------
 template <typename T, int PER>
-__global__ __launch_bounds__(kRowThreads) void reduce_add_norm_kernel(const float *part, int n_split, int m_pad, int ldp,
+__global__ __launch_bounds__(kNormThreads) void reduce_add_norm_kernel(const float *part, int n_split, int m_pad, int ldp,
                                                                       int d, int residual, const T *norm_w, float eps,
                                                                       float *h, T *x) {
   __shared__ float sh[16];
@@ -149,12 +151,22 @@ __global__ __launch_bounds__(kRowThreads) void reduce_add_norm_kernel(const floa
   f32x4_t v[PER];
 #pragma unroll
   for (int e = 0; e < PER; e++) {
-    const int c = (e * kRowThreads + threadIdx.x) * 4;
+    const int c = (e * kNormThreads + threadIdx.x) * 4;
     f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
     if (c < d) {
-      acc = *(const f32x4_t *)(part + (size_t)i * ldp + c);
-      for (int s = 1; s < n_split; s++) acc += *(const f32x4_t *)(part + ((size_t)s * m_pad + i) * ldp + c);   // fixed split order
-      if (residual) acc = *(const f32x4_t *)(h_row + c) + acc;
+      // all loads first (independent, clamped to a valid split), then the sum in ascending split order
+      f32x4_t p[8];
+      const f32x4_t res = *(const f32x4_t *)(h_row + c);
+#pragma unroll
+      for (int s = 0; s < 8; s++) p[s] = *(const f32x4_t *)(part + ((size_t)(s < n_split ? s : 0) * m_pad + i) * ldp + c);
+      acc = p[0];
+#pragma unroll
+      for (int s = 1; s < 8; s++) {
+        const float k = s < n_split ? 1.f : 0.f;            // absent splits add exactly zero
+        acc += p[s] * k;
+      }
+      for (int s = 8; s < n_split; s++) acc += *(const f32x4_t *)(part + ((size_t)s * m_pad + i) * ldp + c);
+      if (residual) acc = res + acc;
     }
     v[e] = acc;
   }
@@ -164,19 +176,19 @@ __global__ __launch_bounds__(kRowThreads) void reduce_add_norm_kernel(const floa
 template <typename T, int PER>
 static void reduce_add_norm_launch(const float *part, int n_split, int m_pad, int ldp, int rows, int d, int residual,
                                    const void *norm_w, float eps, float *h, void *x, hipStream_t st) {
-  hipLaunchKernelGGL((reduce_add_norm_kernel<T, PER>), dim3(rows), dim3(kRowThreads), 0, st, part, n_split, m_pad, ldp, d,
+  hipLaunchKernelGGL((reduce_add_norm_kernel<T, PER>), dim3(rows), dim3(kNormThreads), 0, st, part, n_split, m_pad, ldp, d,
                      residual, (const T *)norm_w, eps, h, (T *)x);
 }
 
 hipError_t launch_reduce_add_norm(int dtype, const float *part, int n_split, int m_pad, int ldp, int rows, int d,
                                   int residual, const void *norm_w, float eps, float *h, void *x, hipStream_t st) {
-  if (rows < 1 || d < 4 || d % 4 || ldp % 4 || d > kRowThreads * 4 * 16) return hipErrorInvalidValue;
-  const int per = (d + kRowThreads * 4 - 1) / (kRowThreads * 4);
+  if (rows < 1 || d < 4 || d % 4 || ldp % 4 || d > kNormThreads * 4 * 4) return hipErrorInvalidValue;
+  const int per = (d + kNormThreads * 4 - 1) / (kNormThreads * 4);
 #define SPEC_RAN(T, P) reduce_add_norm_launch<T, P>(part, n_split, m_pad, ldp, rows, d, residual, norm_w, eps, h, x, st)
   if (dtype == 1) {
-    if (per <= 4) SPEC_RAN(bf16_t, 4); else if (per <= 8) SPEC_RAN(bf16_t, 8); else SPEC_RAN(bf16_t, 16);
+    if (per <= 1) SPEC_RAN(bf16_t, 1); else if (per <= 2) SPEC_RAN(bf16_t, 2); else SPEC_RAN(bf16_t, 4);
   } else {
-    if (per <= 4) SPEC_RAN(float, 4); else if (per <= 8) SPEC_RAN(float, 8); else SPEC_RAN(float, 16);
+    if (per <= 1) SPEC_RAN(float, 1); else if (per <= 2) SPEC_RAN(float, 2); else SPEC_RAN(float, 4);
   }
 #undef SPEC_RAN
   return hipGetLastError();
