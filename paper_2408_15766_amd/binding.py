@@ -72,6 +72,7 @@ lib.spec_get_features.argtypes = [C.c_void_p, _f32p, C.c_int64]
 lib.spec_get_kv.restype = C.c_int64
 lib.spec_get_kv.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, _f32p, _f32p, C.c_int64]
 lib.spec_set_profile.argtypes = [C.c_void_p, C.c_int32]
+lib.spec_set_graphs.argtypes = [C.c_void_p, C.c_int32]
 lib.spec_get_profile.argtypes = [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_int64)]
 lib.spec_last_error.restype = C.c_char_p
 lib.spec_last_error.argtypes = [C.c_void_p]
@@ -179,6 +180,10 @@ def spec_get_kv(ctx, which: int, layer: int, n_rows: int, d_kv: int):
     v = np.empty((n_rows, d_kv), dtype=np.float32)
     _check(ctx, lib.spec_get_kv(ctx, which, layer, n_rows, k.ctypes.data_as(_f32p), v.ctypes.data_as(_f32p), k.size))
     return k, v
+
+
+def spec_set_graphs(ctx, enable: bool) -> None:
+    _check(ctx, lib.spec_set_graphs(ctx, 1 if enable else 0))
 
 
 def spec_set_profile(ctx, level: int) -> None:
@@ -299,9 +304,12 @@ class Engine:
     """Owns the torch-allocated workspace and the weight pointer table of one libspec context."""
 
     def __init__(self, shape, weights: Dict[str, "object"], *, max_seq: Optional[int] = None, temperature: Optional[float] = None,
-                 seed: int = 0, tree=None, device: int = 0):
+                 seed: int = 0, tree=None, device: int = 0, graphs: bool = True):
         import torch
         self.shape = shape
+        # a stream of its own (default priority): graph capture is not possible on the default stream
+        torch.cuda.synchronize(device)                  # weights were produced on torch's current stream
+        self.stream = torch.cuda.Stream(device=device)
         self.weights = weights                         # keeps the tensors alive: the library borrows them
         depth, topk, total = tree if tree is not None else (shape.tree_depth, shape.tree_topk, shape.tree_total)
         self.total = total
@@ -310,7 +318,7 @@ class Engine:
         cfg = spec_config(shape.n_layers, shape.d_model, shape.n_q_heads, shape.n_kv_heads, shape.head_dim, shape.d_ffn, shape.vocab,
                           shape.rope_theta, shape.rms_eps, 1 if shape.dtype == "bf16" else 0, max_seq, depth, topk, total,
                           shape.temperature if temperature is None else temperature, seed, device,
-                          torch.cuda.current_stream(device).cuda_stream, None, 0)
+                          self.stream.cuda_stream, None, 0)
         nbytes = spec_workspace_bytes(cfg)
         if nbytes == 0:
             raise SpecError(SPEC_EINVAL, "invalid configuration")
@@ -331,7 +339,10 @@ class Engine:
         for f in LAYER_FIELDS:
             setattr(w.draft_layer, f, weights[f"draft.{f}"].data_ptr())
         self._w = w
+        torch.cuda.synchronize(device)                  # workspace zero-fill done before the library's stream uses it
         self.ctx = spec_create(cfg, w)
+        if not graphs:
+            spec_set_graphs(self.ctx, False)
         self.tree = Tree.empty(max(total, 1))
 
     def close(self):

@@ -31,6 +31,7 @@ struct RowTables {                    // device index tables describing the rows
 
 struct HostStage {                    // pinned host staging, one allocation
   int tree_n;
+  int base;                           // committed tokens at the time of the verify (read by replayed kernels)
   int tok[kMaxNodes], par[kMaxNodes], dep[kMaxNodes];
   float sc[kMaxNodes];
   int pos[kMaxNodes], slot[kMaxNodes];
@@ -72,12 +73,17 @@ struct spec_ctx {
   int *d_prompt = nullptr, *d_pos = nullptr, *d_slot = nullptr, *d_depth = nullptr;
   int *pend_tok = nullptr, *root_tok = nullptr, *row_argmax = nullptr;
   // verify tree on the device: packed exactly like the head of HostStage (tree_n .. anc)
-  int *t_n = nullptr, *t_tok = nullptr, *t_par = nullptr, *t_dep = nullptr, *t_pos = nullptr, *t_slot = nullptr, *t_anc = nullptr;
+  int *t_n = nullptr, *t_base = nullptr, *t_tok = nullptr, *t_par = nullptr, *t_dep = nullptr, *t_pos = nullptr, *t_slot = nullptr, *t_anc = nullptr;
   float *t_sc = nullptr;
   DraftState ds{};
   AcceptResult *acc = nullptr;
   HostStage *stage = nullptr;
   size_t part_floats = 0;
+
+  // HIP graph of the verify forward (replayed every cycle; needs a non-default stream)
+  bool graphs = true;
+  hipGraphExec_t verify_exec = nullptr;
+  int verify_exec_rows = 0;
 
   // profiling
   int prof_level = 0;
@@ -210,6 +216,7 @@ size_t layout(const spec_config &c, spec_ctx *x, char *base) {
     if (x) {
       char *b = base + o_;
       x->t_n = (int *)(b + offsetof(HostStage, tree_n));
+      x->t_base = (int *)(b + offsetof(HostStage, base));
       x->t_tok = (int *)(b + offsetof(HostStage, tok));
       x->t_par = (int *)(b + offsetof(HostStage, par));
       x->t_dep = (int *)(b + offsetof(HostStage, dep));
@@ -301,7 +308,7 @@ int run_gemm(spec_ctx *c, const void *x, int ldx, int m, int in, const Seg *segs
 // One decoder layer over m rows.  In: c->h (fp32 residual stream) and c->x (rows normed by the
 // layer's attn_norm).  Out: c->h updated; x_out = rmsnorm(h) * next_norm (or h itself, cast).
 int layer_forward(spec_ctx *c, const spec_layer_weights &lw, char *kcache, char *vcache, int m, int base,
-                  const RowTables &rt, int max_pos, const void *next_norm, void *x_out) {
+                  const RowTables &rt, int max_pos, const void *next_norm, void *x_out, const int *base_ptr = nullptr) {
   const spec_config &g = c->cfg;
   const int d = g.d_model, dq = g.n_q_heads * g.head_dim, dkv = g.n_kv_heads * g.head_dim, f = g.d_ffn;
   const int dt = g.dtype;
@@ -316,7 +323,7 @@ int layer_forward(spec_ctx *c, const spec_layer_weights &lw, char *kcache, char 
   {
     AttnArgs a{};
     a.q = c->qbuf; a.kcache = kcache; a.vcache = vcache;
-    a.rows = m; a.hq = g.n_q_heads; a.hkv = g.n_kv_heads; a.hd = g.head_dim; a.base = base;
+    a.rows = m; a.hq = g.n_q_heads; a.hkv = g.n_kv_heads; a.hd = g.head_dim; a.base = base; a.base_ptr = base_ptr;
     a.depth = rt.depth; a.anc = rt.anc;
     a.scale = 1.0f / sqrtf((float)g.head_dim);
     a.part = c->attn_part; a.max_parts = c->max_parts; a.out = c->attn_out;
@@ -356,7 +363,9 @@ int lm_head(spec_ctx *c, const void *x, int rows, float *logits) {
 }
 
 // Target model over m rows -> c->feats [m, d] (final-norm output) and the updated target cache.
-int target_forward(spec_ctx *c, int m, int base, const RowTables &rt, int max_pos) {
+// With base_ptr set, the base comes from device memory and max_pos is only an upper bound for grid
+// sizes: the launch sequence is then independent of the cycle and can be captured into a graph.
+int target_forward(spec_ctx *c, int m, int base, const RowTables &rt, int max_pos, const int *base_ptr = nullptr) {
   const spec_config &g = c->cfg;
   HIPCHK(c, launch_rope_table(rt.pos, m, g.head_dim, g.rope_theta, c->rope, c->stream));
   HIPCHK(c, launch_embed_norm(g.dtype, c->w.embed, rt.token, m, g.d_model, c->layers[0].attn_norm, g.rms_eps, c->h, c->x, c->stream));
@@ -365,7 +374,7 @@ int target_forward(spec_ctx *c, int m, int base, const RowTables &rt, int max_po
     char *vc = kc + c->t_kv_stride * c->esz;
     const bool last = l + 1 == g.n_layers;
     int rc = layer_forward(c, c->layers[l], kc, vc, m, base, rt, max_pos, last ? c->w.final_norm : c->layers[l + 1].attn_norm,
-                           last ? c->feats : c->x);
+                           last ? c->feats : c->x, base_ptr);
     if (rc) return rc;
   }
   return SPEC_OK;
@@ -439,6 +448,7 @@ int spec_create(const spec_config *cfg, const spec_weights *w, spec_ctx **out) {
   c->stream = (hipStream_t)cfg->stream;
   layout(*cfg, c, (char *)cfg->workspace);
   hipError_t e = hipSetDevice(cfg->device);
+  if (e == hipSuccess) e = gemm_init();
   if (e == hipSuccess) e = hipHostMalloc((void **)&c->stage, sizeof(HostStage), hipHostMallocDefault);
   if (e != hipSuccess) {
     int rc = fail(nullptr, SPEC_EHIP, "device %d / pinned staging: %s", cfg->device, hipGetErrorString(e));
@@ -457,6 +467,7 @@ void spec_destroy(spec_ctx *c) {
   for (int p = 0; p < 4; p++)
     for (int k = 0; k < 2; k++) if (c->ev_phase[p][k]) (void)hipEventDestroy(c->ev_phase[p][k]);
   for (hipEvent_t e : c->ev_gemm) (void)hipEventDestroy(e);
+  if (c->verify_exec) (void)hipGraphExecDestroy(c->verify_exec);
   if (c->stage) (void)hipHostFree(c->stage);
   delete c;
 }
@@ -600,15 +611,38 @@ int spec_verify(spec_ctx *c, const spec_tree *tree) {
     max_depth = std::max(max_depth, dep);
   }
   s.tree_n = N;
+  s.base = c->n;
   HIPCHK(c, hipSetDevice(g.device));
   phase_begin(c, 1);
   c->gemm_bucket = 4;
   HIPCHK(c, hipMemcpyAsync(c->t_n, &s.tree_n, offsetof(HostStage, acc), hipMemcpyHostToDevice, c->stream));
   RowTables rt{c->t_tok, c->t_pos, c->t_slot, c->t_dep, c->t_anc};
-  int rc = target_forward(c, N, c->n, rt, c->n + max_depth);
-  if (rc) return rc;
-  rc = lm_head(c, c->feats, N, c->logits);
-  if (rc) return rc;
+  int rc;
+  const bool use_graph = c->graphs && c->stream != nullptr && c->prof_level < 2 && N == g.tree_total;
+  if (use_graph) {
+    // Every launch argument of the forward is either fixed or read from device memory (the tree
+    // tables and the base), so the sequence is captured once and replayed each cycle.
+    if (c->verify_exec == nullptr || c->verify_exec_rows != N) {
+      if (c->verify_exec) { (void)hipGraphExecDestroy(c->verify_exec); c->verify_exec = nullptr; }
+      hipGraph_t graph = nullptr;
+      HIPCHK(c, hipStreamBeginCapture(c->stream, hipStreamCaptureModeThreadLocal));
+      rc = target_forward(c, N, 0, rt, g.max_seq - 1, c->t_base);
+      if (!rc) rc = lm_head(c, c->feats, N, c->logits);
+      hipError_t e = hipStreamEndCapture(c->stream, &graph);
+      if (rc) { if (graph) (void)hipGraphDestroy(graph); return rc; }
+      if (e != hipSuccess) return fail(c, SPEC_EHIP, "graph capture: %s", hipGetErrorString(e));
+      e = hipGraphInstantiate(&c->verify_exec, graph, nullptr, nullptr, 0);
+      (void)hipGraphDestroy(graph);
+      if (e != hipSuccess) { c->verify_exec = nullptr; return fail(c, SPEC_EHIP, "graph instantiate: %s", hipGetErrorString(e)); }
+      c->verify_exec_rows = N;
+    }
+    HIPCHK(c, hipGraphLaunch(c->verify_exec, c->stream));
+  } else {
+    rc = target_forward(c, N, c->n, rt, c->n + max_depth);
+    if (rc) return rc;
+    rc = lm_head(c, c->feats, N, c->logits);
+    if (rc) return rc;
+  }
   c->gemm_bucket = 0;
   phase_end(c, 1);
   c->last_nodes = N;
@@ -706,6 +740,12 @@ int64_t spec_get_kv(spec_ctx *c, int32_t which, int32_t layer, int32_t n_rows, f
   int64_t r = copy_widen(c, k, n, k_dst);
   if (r < 0) return r;
   return copy_widen(c, v, n, v_dst);
+}
+
+int spec_set_graphs(spec_ctx *c, int32_t enable) {
+  if (!c) return SPEC_EINVAL;
+  c->graphs = enable != 0;
+  return SPEC_OK;
 }
 
 int spec_set_profile(spec_ctx *c, int32_t level) {

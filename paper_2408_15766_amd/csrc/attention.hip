@@ -66,7 +66,8 @@ __global__ __launch_bounds__(64) void attn_part_kernel(AttnArgs a) {
   __shared__ __attribute__((aligned(16))) float qs[G][HD];
   __shared__ __attribute__((aligned(16))) unsigned char vs[64 * VROW];
   const int i = blockIdx.x, hk = blockIdx.y, part = blockIdx.z, lane = threadIdx.x;
-  const int p = a.base + a.depth[i];
+  const int base = a.base_ptr ? *a.base_ptr : a.base;  // device-resident when the launch is replayed from a graph
+  const int p = base + a.depth[i];
   // full mode: part `part` of the whole range [0, p]; tail mode: the single range [A(p), p]
   const int k_lo = a.tail_only ? bulk_end(p) : part * kAttnPart;
   const int k_hi = a.tail_only ? p + 1 : min(p + 1, k_lo + kAttnPart);
@@ -93,7 +94,7 @@ __global__ __launch_bounds__(64) void attn_part_kernel(AttnArgs a) {
     const int kq = kb + lane;
     const bool valid = kq < k_hi;
     int slot = 0;
-    if (valid) slot = kq < a.base ? kq : a.base + (anc ? anc[kq - a.base] : kq - a.base);
+    if (valid) slot = kq < base ? kq : base + (anc ? anc[kq - base] : kq - base);
     const T *kptr = kbase + (size_t)slot * row_stride;
     const T *vptr = vbase + (size_t)slot * row_stride;
     u32x4_t kc[HD / EPL], vc[HD / EPL];
@@ -164,7 +165,7 @@ __global__ __launch_bounds__(64) void attn_part_kernel(AttnArgs a) {
 template <typename T, int HD>
 __global__ void attn_combine_kernel(AttnArgs a) {
   const int i = blockIdx.x, h = blockIdx.y, d = threadIdx.x;
-  const int p = a.base + a.depth[i];
+  const int p = (a.base_ptr ? *a.base_ptr : a.base) + a.depth[i];
   // full mode: parts 0 .. p/kAttnPart; hybrid mode: the bulk parts that hold keys of this row, then the tail slot
   const int n_parts = a.tail_only ? (bulk_end(p) + kAttnPart - 1) / kAttnPart : p / kAttnPart + 1;
   const float *src = a.part + ((size_t)i * a.hq + h) * a.max_parts * (HD + 2);
@@ -223,14 +224,18 @@ __global__ __launch_bounds__(NW * 64) void attn_bulk_kernel(AttnArgs a) {
 
   const int part = blockIdx.x, hk = blockIdx.y;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, c = lane & 31, g = lane >> 5;
+  // With a device-resident base (graph replay) the grid is sized for the longest context and the
+  // blocks that exist are derived here; otherwise the host has computed them.
+  const int base = a.base_ptr ? *a.base_ptr : a.base;
+  const int n_blocks = a.base_ptr ? min(a.bulk_blocks, bulk_end(base + kMaxDepth) / 32) : a.bulk_blocks;
   const int b_lo = part * kBulkBlocksPerPart;
-  const int b_hi = min(b_lo + kBulkBlocksPerPart, a.bulk_blocks);
+  const int b_hi = min(b_lo + kBulkBlocksPerPart, n_blocks);
   if (b_lo >= b_hi) return;
 
   const int r = (blockIdx.z * NW + wave) * 32 + c;
   const bool valid_q = r < a.rows * G;
   const int i = valid_q ? r / G : 0, gh = valid_q ? r % G : 0;
-  const int n_incl = valid_q ? bulk_end(a.base + a.depth[i]) / 32 : 0;      // blocks [0, n_incl) belong to this row
+  const int n_incl = valid_q ? bulk_end(base + a.depth[i]) / 32 : 0;        // blocks [0, n_incl) belong to this row
 
   // query fragments: step kk covers dims kk*16 + g*8 .. +8
   u32x4_t qhi[KK], qlo[KK];

@@ -256,21 +256,35 @@ hipError_t launch_pack_weight(int dtype, const void *src, int rows, int in, void
   return hipGetLastError();
 }
 
+// The double-buffered slab exceeds the 64 KiB default for dynamic LDS from two token blocks on: raise the
+// limit once per kernel, at context creation (never during a stream capture).
+template <typename T>
+static hipError_t init_t() {
+  const void *fn[4] = {(const void *)gemm_stream_kernel<T, 1>, (const void *)gemm_stream_kernel<T, 2>,
+                       (const void *)gemm_stream_kernel<T, 3>, (const void *)gemm_stream_kernel<T, 4>};
+  for (int tb = 1; tb <= 4; tb++) {
+    const size_t lds = (size_t)2 * tb * 32 * kSlabStride;
+    if (lds > 160 * 1024) continue;
+    hipError_t e = hipFuncSetAttribute(fn[tb - 1], hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+  }
+  return hipSuccess;
+}
+hipError_t gemm_init() {
+  static bool done = false;
+  if (done) return hipSuccess;
+  hipError_t e = init_t<bf16_t>();
+  if (e == hipSuccess) e = init_t<float>();
+  done = e == hipSuccess;
+  return e;
+}
+
 template <typename T>
 static hipError_t launch_t(const GemmArgs &a, hipStream_t st) {
   const int tb = (a.m + 31) / 32;
   dim3 grid((a.total_blocks + kGemmWaves - 1) / kGemmWaves, a.n_split);
   const size_t lds = (size_t)2 * tb * 32 * kSlabStride;
-  // the double-buffered slab exceeds the 64 KiB default for dynamic LDS from two token blocks on
-  static bool attr_set[5] = {false, false, false, false, false};
   if (lds > 160 * 1024) return hipErrorInvalidValue;
-  if (!attr_set[tb]) {
-    const void *fn = tb == 1 ? (const void *)gemm_stream_kernel<T, 1> : tb == 2 ? (const void *)gemm_stream_kernel<T, 2>
-                   : tb == 3 ? (const void *)gemm_stream_kernel<T, 3> : (const void *)gemm_stream_kernel<T, 4>;
-    hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    if (e != hipSuccess) return e;
-    attr_set[tb] = true;
-  }
   switch (tb) {
     case 1: hipLaunchKernelGGL((gemm_stream_kernel<T, 1>), grid, dim3(kGemmThreads), lds, st, a); break;
     case 2: hipLaunchKernelGGL((gemm_stream_kernel<T, 2>), grid, dim3(kGemmThreads), lds, st, a); break;
@@ -286,6 +300,7 @@ int gemm_k_per_slab(int dtype) { return kSlabIters * gemm_k_per_iter(dtype); }
 int gemm_rows_per_group() { return 32 * kGemmWaves; }
 
 hipError_t launch_gemm(int dtype, const GemmArgs &a, hipStream_t st) {
+  { hipError_t e = gemm_init(); if (e != hipSuccess) return e; }
   if (a.m < 1 || a.m > 128 || a.nseg < 1 || a.nseg > 3 || a.n_split < 1 || a.in < 1) return hipErrorInvalidValue;
   if (a.n_split > (a.in + gemm_k_per_slab(dtype) - 1) / gemm_k_per_slab(dtype)) return hipErrorInvalidValue;   // no empty split
   return dtype == 1 ? launch_t<bf16_t>(a, st) : launch_t<float>(a, st);

@@ -26,6 +26,7 @@ struct GemmArgs {
   int n_split;                          // K is cut into n_split ranges of whole slabs, balanced to one slab
 };
 hipError_t launch_gemm(int dtype, const GemmArgs &a, hipStream_t st);
+hipError_t gemm_init();                 // one-time kernel attributes; call outside any stream capture
 int gemm_k_per_slab(int dtype);
 int gemm_k_per_iter(int dtype);
 int gemm_rows_per_group();
@@ -66,6 +67,7 @@ struct AttnArgs {
   const void *q;                        // fp32 [rows, hq*hd]
   const void *kcache; const void *vcache;
   int rows, hq, hkv, hd, base;
+  const int *base_ptr;                  // if not null: the base is read from here (device) and `base` is ignored
   const int *depth;                     // [rows]
   const int *anc;                       // [rows][kAncStride] or nullptr
   float scale;
