@@ -252,3 +252,80 @@ def test_graph_replay_equals_eager_launches(env, bf16_model):
     assert ta == tb == greedy[:gen] and ua == ub and len(ra) == len(rb) >= 4
     for a, b in zip(ra, rb):
         assert np.array_equal(a["logits"], b["logits"]) and np.array_equal(a["feats"], b["feats"])
+
+
+def test_bf16_sampling_acceptance_matches_oracle_on_gpu_logits(env, bf16_model):
+    """T = 1 at real vocabulary sizes (the LLaMA2-13B configuration's mode): the GPU's rejection-sampling
+    decisions must equal the oracle's acceptance run on the GPU's own fp32 logits, cycle by cycle."""
+    torch, P = env
+    sh, hw, dw, prompt = bf16_model
+    temp = 1.0
+    for seed in (11, 12):
+        eng = P.Engine(sh, dw, temperature=temp, seed=seed)
+        eng.prefill(prompt)
+        for cycle in range(1, 5):
+            t = eng.draft_tree()
+            eng.verify(t)
+            lg = eng.logits(t.n_nodes)
+            ot = oracle.Tree(t.token[:t.n_nodes].copy(), t.parent[:t.n_nodes].copy(), t.depth[:t.n_nodes].copy(), t.score[:t.n_nodes].copy())
+            acc, bonus = oracle.accept_sample(ot, lg, temp, seed, cycle)
+            assert eng.accept(t) == [int(ot.token[j]) for j in acc] + [bonus]
+    # low temperature: the distribution is peaky, rejection tests are decided by real probabilities
+    eng = P.Engine(sh, dw, temperature=0.3, seed=5)
+    eng.prefill(prompt)
+    for cycle in range(1, 4):
+        t = eng.draft_tree()
+        eng.verify(t)
+        lg = eng.logits(t.n_nodes)
+        ot = oracle.Tree(t.token[:t.n_nodes].copy(), t.parent[:t.n_nodes].copy(), t.depth[:t.n_nodes].copy(), t.score[:t.n_nodes].copy())
+        acc, bonus = oracle.accept_sample(ot, lg, 0.3, 5, cycle)
+        assert eng.accept(t) == [int(ot.token[j]) for j in acc] + [bonus]
+
+
+LONG_GQA = wl.LLAMA3_8B.with_(name="llama3-8b-width-2layer-long", n_layers=2, vocab=8192, d_ffn=4096, prompt_len=4096, gen_tokens=12)
+
+
+def test_long_context_spec_equals_greedy_bit_exact(env):
+    """The LLaMA3-8B configuration's long-KV verify (4096-token prompt, GQA 32/8): speculative decoding with
+    forged acceptance equals plain decoding token for token and in the root row's logit bits."""
+    torch, P = env
+    sh = LONG_GQA
+    dw = P.pack_weights(wl.iter_device_weights(sh, "cuda"))
+    prompt = wl.make_prompt(sh)
+    gen = sh.gen_tokens
+    plain = P.Engine(sh, dw, tree=(1, 1, 1))
+    prec = []
+    greedy, _ = plain.generate(prompt, gen + 8, record=prec)
+    rng = np.random.default_rng(1)
+    spec = P.Engine(sh, dw)
+    srec = []
+    got, taus = spec.generate(prompt, gen, tree_hook=forge_hook(greedy, len(prompt), lambda n: (n * 7) % 6, rng, sh.vocab), record=srec)
+    assert got == greedy[:gen] and max(taus) >= 4
+    plain_at = {r["n"]: r["logits"][0] for r in prec}
+    for r in srec:
+        assert np.array_equal(r["logits"][0], plain_at[r["n"]])
+
+
+def test_full_depth_7b_bench_configuration(env):
+    """BASELINE's LLaMA2-7B configuration at full size, in the launch configuration bench.py times (device-drawn
+    weights, graph replay): (1) speculative == plain decoding for 12 tokens with forged acceptance; (2) sampled
+    logits of the LM head equal the oracle's dot products of the GPU's feature rows with the head's rows."""
+    torch, P = env
+    sh = wl.LLAMA2_7B
+    named = dict(wl.iter_device_weights(sh, "cuda"))
+    head_rows = {v: named["lm_head"][v].float().cpu().numpy() for v in (0, 1, 777, 31999)}
+    dw = P.pack_weights(named.items())
+    del named
+    prompt = wl.make_prompt(sh)
+    gen = 12
+    plain = P.Engine(sh, dw, tree=(1, 1, 1))
+    greedy, _ = plain.generate(prompt, gen + 8)
+    rng = np.random.default_rng(2)
+    spec = P.Engine(sh, dw)
+    rec = []
+    got, taus = spec.generate(prompt, gen, tree_hook=forge_hook(greedy, len(prompt), lambda n: n % 4, rng, sh.vocab), record=rec)
+    assert got == greedy[:gen] and max(taus) >= 3
+    r = rec[-1]
+    for v, w_row in head_rows.items():
+        want = r["feats"].astype(np.float64) @ w_row.astype(np.float64)
+        assert np.abs(r["logits"][:, v] - want).max() < 2e-3

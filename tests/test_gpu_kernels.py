@@ -168,3 +168,39 @@ def test_topk_logprob_matches_oracle(env, rows, vocab, k):
         assert list(tok[r]) == list(want)
         assert np.abs(lp[r] - want_lp[r, want]).max() < 5e-6
     assert tok[0, 0] == 7 and tok[0, 1] == 900 and (rows == 1 or tok[-1, 0] == vocab - 1)
+
+
+@pytest.mark.parametrize("name,rows,k,n_split", [("70b-down", 8192, 28672, 4), ("70b-gateup-slice", 4096, 8192, 1), ("13b-qkv-slice", 5120, 5120, 2)])
+def test_gemm_large_shapes_sampled_against_oracle(env, name, rows, k, n_split):
+    """Matrix shapes of the largest configurations, M = 60: sampled output columns against fp64 dot products."""
+    torch, P = env
+    g = torch.Generator(device="cuda"); g.manual_seed(5)
+    x = (torch.randn(60, k, device="cuda", generator=g)).to(torch.bfloat16)
+    w = (torch.randn(rows, k, device="cuda", generator=g) * 0.02).to(torch.bfloat16)
+    got = P.spec_k_gemm(x, [w], n_split).sum(dim=0).cpu().numpy().astype(np.float64)
+    cols = [0, 1, 31, 32, rows // 2 + 5, rows - 33, rows - 1]
+    xs = x.float().cpu().numpy().astype(np.float64)
+    for c in cols:
+        want = xs @ w[c].float().cpu().numpy().astype(np.float64)
+        assert np.abs(got[:, c] - want).max() < 2e-3
+
+
+def test_attention_long_context_matches_oracle(env):
+    """Long-KV verify of the LLaMA3-8B configuration: 4100 cached keys, GQA 4:1, sampled rows and heads."""
+    torch, P = env
+    rng = np.random.default_rng(77)
+    hq, hkv, hd, base, rows = 8, 2, 128, 4100, 60
+    par, dep, anc = make_tree(rng, rows, 6)
+    q = rand_storage(rng, (rows, hq * hd), "bf16")
+    kc = rand_storage(rng, (base + rows, hkv * hd), "bf16")
+    vc = rand_storage(rng, (base + rows, hkv * hd), "bf16")
+    out = P.spec_k_attention(to_dev(torch, q, "fp32"), to_dev(torch, kc, "bf16"), to_dev(torch, vc, "bf16"), base,
+                             torch.from_numpy(dep).cuda(), torch.from_numpy(anc).cuda(), hq, hkv, hd)
+    got = out.float().cpu().numpy().reshape(rows, hq, hd)
+    k3, v3 = kc.reshape(-1, hkv, hd).astype(np.float64), vc.reshape(-1, hkv, hd).astype(np.float64)
+    q3 = q.reshape(rows, hq, hd).astype(np.float64)
+    for i in (0, 1, 17, 59):
+        vis = list(range(base)) + [base + a for a in anc[i, :dep[i] + 1]]
+        for h in (0, 3, 7):
+            want = attention_row(q3[i, h], k3[vis, h // 4], v3[vis, h // 4])
+            assert np.abs(got[i, h] - want).max() < 2e-2
