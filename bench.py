@@ -20,6 +20,9 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0
+# HBM bytes per GEMM launch (fetch + write) measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by a
+# plain-copy calibration: see profiles/traffic_gemm_stream_<workload>.txt.  None where not measured.
+MEASURED_TRAFFIC_BYTES_PER_LAUNCH = {"llama2-7b": 114.5e6}
 
 
 def parse():
@@ -31,6 +34,8 @@ def parse():
     ap.add_argument("--layers", type=int, default=0, help="override the number of target layers (0 = the config's)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-roofline-pass", action="store_true", help="skip the instrumented passes (for profilers)")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="only run a plain 1 GiB device copy four times (known traffic, to scale rocprofv3's FETCH_SIZE/WRITE_SIZE)")
     return ap.parse_args()
 
 
@@ -91,6 +96,14 @@ def main():
     import workload as wl
     import paper_2408_15766_amd as P
 
+    if a.calibrate_copy:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")       # 1 GiB
+        dst = torch.empty_like(src)
+        for _ in range(4):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibrate_copy_bytes_read_per_launch": src.numel() * 4, "bytes_written_per_launch": src.numel() * 4}))
+        return
     sh = wl.BY_NAME[a.config]
     if a.layers:
         sh = sh.with_(n_layers=a.layers, name=f"{sh.name}-{a.layers}layer")
@@ -161,7 +174,8 @@ def main():
                 bytes_per_launch = by["verify_weights"] / n_launch
                 achieved = bytes_per_launch / (avg_ms * 1e-3) / 1e9
                 out["roofline"] = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                                   "frac": achieved / HBM_PEAK_GBPS, "traffic": None,
+                                   "frac": achieved / HBM_PEAK_GBPS,
+                                   "traffic": MEASURED_TRAFFIC_BYTES_PER_LAUNCH.get(a.config) if not a.layers else None,
                                    "kernel": "gemm_stream_kernel (verify launches)", "launches_per_step": n_launch,
                                    "avg_launch_ms": avg_ms, "algorithmic_bytes_per_launch": bytes_per_launch}
     if not a.no_cpu_baseline:
