@@ -84,6 +84,7 @@ struct spec_ctx {
   bool graphs = true;
   hipGraphExec_t verify_exec = nullptr;
   int verify_exec_rows = 0;
+  hipGraphExec_t expand_exec = nullptr;   // draft expansion steps 2..D + rerank
 
   // profiling
   int prof_level = 0;
@@ -279,8 +280,9 @@ void harvest_profile(spec_ctx *c) {
 struct Seg { const void *w; int rows; };
 
 int run_gemm(spec_ctx *c, const void *x, int ldx, int m, int in, const Seg *segs, int nseg, float *out, int ldp, int m_pad,
-             const GemmPlan &p) {
+             const GemmPlan &p, void *swiglu_act = nullptr) {
   GemmArgs a{};
+  a.act = swiglu_act;
   a.x = x; a.ldx = ldx; a.m = m; a.in = in; a.nseg = nseg;
   int col = 0, blocks = 0;
   for (int s = 0; s < 3; s++) {
@@ -337,11 +339,18 @@ int layer_forward(spec_ctx *c, const spec_layer_weights &lw, char *kcache, char 
     HIPCHK(c, launch_reduce_add_norm(dt, c->part, p.n_split, c->m_max, d, m, d, 1, lw.ffn_norm, g.rms_eps, c->h, c->x, c->stream));
   }
   {
+    // gate and up projections.  Without a K split a workgroup owns matching gate and up blocks and applies
+    // SwiGLU itself (no partial sums, no extra pass); with a K split the row kernel does it.
     const Seg segs[2] = {{lw.w_gate, f}, {lw.w_up, f}};
     const GemmPlan p = plan_gemm(2 * f, d, dt);
-    int rc = run_gemm(c, c->x, d, m, d, segs, 2, c->part, 2 * f, c->m_max, p);
-    if (rc) return rc;
-    HIPCHK(c, launch_reduce_swiglu(dt, c->part, p.n_split, c->m_max, 2 * f, m, f, c->act, c->stream));
+    if (p.n_split == 1) {
+      int rc = run_gemm(c, c->x, d, m, d, segs, 2, c->part, 2 * f, c->m_max, p, c->act);
+      if (rc) return rc;
+    } else {
+      int rc = run_gemm(c, c->x, d, m, d, segs, 2, c->part, 2 * f, c->m_max, p);
+      if (rc) return rc;
+      HIPCHK(c, launch_reduce_swiglu(dt, c->part, p.n_split, c->m_max, 2 * f, m, f, c->act, c->stream));
+    }
   }
   {
     const Seg segs[1] = {{lw.w_down, d}};
@@ -381,7 +390,8 @@ int target_forward(spec_ctx *c, int m, int base, const RowTables &rt, int max_po
 }
 
 // Draft model over m rows of (feature, token) -> c->gfeat [m, d] (predicted features, no norm).
-int draft_forward(spec_ctx *c, int m, int base, const void *feat, const int *src_row, const RowTables &rt, int max_pos) {
+int draft_forward(spec_ctx *c, int m, int base, const void *feat, const int *src_row, const RowTables &rt, int max_pos,
+                  const int *base_ptr = nullptr) {
   const spec_config &g = c->cfg;
   const int d = g.d_model;
   HIPCHK(c, launch_rope_table(rt.pos, m, g.head_dim, g.rope_theta, c->rope, c->stream));
@@ -394,7 +404,7 @@ int draft_forward(spec_ctx *c, int m, int base, const void *feat, const int *src
                                    c->x, c->stream));
   char *kc = c->kv_d;
   char *vc = kc + c->d_kv_stride * c->esz;
-  return layer_forward(c, c->w.draft_layer, kc, vc, m, base, rt, max_pos, nullptr, c->gfeat);
+  return layer_forward(c, c->w.draft_layer, kc, vc, m, base, rt, max_pos, nullptr, c->gfeat, base_ptr);
 }
 
 int sync(spec_ctx *c) {
@@ -468,6 +478,7 @@ void spec_destroy(spec_ctx *c) {
     for (int k = 0; k < 2; k++) if (c->ev_phase[p][k]) (void)hipEventDestroy(c->ev_phase[p][k]);
   for (hipEvent_t e : c->ev_gemm) (void)hipEventDestroy(e);
   if (c->verify_exec) (void)hipGraphExecDestroy(c->verify_exec);
+  if (c->expand_exec) (void)hipGraphExecDestroy(c->expand_exec);
   if (c->stage) (void)hipHostFree(c->stage);
   delete c;
 }
@@ -518,6 +529,8 @@ int spec_prefill(spec_ctx *c, const int32_t *prompt, int32_t n_prompt, int32_t *
       if (rc) return rc;
     }
   }
+  c->stage->base = n_prompt;
+  HIPCHK(c, hipMemcpyAsync(c->t_base, &c->stage->base, 4, hipMemcpyHostToDevice, c->stream));
   HIPCHK(c, hipMemcpyAsync(&c->stage->first_token, c->root_tok, 4, hipMemcpyDeviceToHost, c->stream));
   phase_end(c, 3);
   int rc = sync(c);
@@ -557,19 +570,41 @@ int spec_draft_tree(spec_ctx *c, spec_tree *out) {
   rc = lm_head(c, (const char *)c->gfeat + (size_t)(m1 - 1) * d * c->esz, 1, c->dlogits);
   if (rc) return rc;
   HIPCHK(c, launch_rows_topk_logprob(c->dlogits, 1, g.vocab, K, c->sc_val, c->sc_idx, c->sc_stat, c->top_tok, c->top_lp, c->stream));
-  HIPCHK(c, launch_pool_init(c->ds, c->top_tok, c->top_lp, K, m1 - 1, c->n, c->stream));
-  // expansion steps 2..D: the frontier's k nodes, each fed (parent's predicted feature, own token)
-  for (int t = 2; t <= D; t++) {
-    RowTables fr{c->ds.front_tok, c->ds.front_pos, c->ds.front_slot, c->ds.front_depth, c->ds.front_anc};
-    // xcat is built from gfeat before the layer overwrites gfeat, so one buffer serves all steps
-    rc = draft_forward(c, K, c->n, c->gfeat, c->ds.front_src, fr, c->n + t - 2);
+  HIPCHK(c, launch_pool_init(c->ds, c->top_tok, c->top_lp, K, m1 - 1, c->t_base, c->stream));
+  // expansion steps 2..D (the frontier's k nodes, each fed (parent's predicted feature, own token)) and
+  // the rerank.  Every argument is fixed or device-resident (frontier tables, committed count), so the
+  // whole sequence is captured once and replayed.
+  auto expand_all = [&](const int *base_ptr, int base, int pos_bound) -> int {
+    for (int t = 2; t <= D; t++) {
+      RowTables fr{c->ds.front_tok, c->ds.front_pos, c->ds.front_slot, c->ds.front_depth, c->ds.front_anc};
+      // xcat is built from gfeat before the layer overwrites gfeat, so one buffer serves all steps
+      int r = draft_forward(c, K, base, c->gfeat, c->ds.front_src, fr, base_ptr ? pos_bound : base + t - 2, base_ptr);
+      if (r) return r;
+      r = lm_head(c, c->gfeat, K, c->dlogits);
+      if (r) return r;
+      HIPCHK(c, launch_rows_topk_logprob(c->dlogits, K, g.vocab, K, c->sc_val, c->sc_idx, c->sc_stat, c->top_tok, c->top_lp, c->stream));
+      HIPCHK(c, launch_pool_expand(c->ds, c->top_tok, c->top_lp, K, t, c->t_base, t < D ? 1 : 0, c->stream));
+    }
+    HIPCHK(c, launch_rerank(c->ds, g.tree_total, c->root_tok, c->t_n, c->t_tok, c->t_par, c->t_dep, c->t_sc, c->stream));
+    return SPEC_OK;
+  };
+  if (c->graphs && c->stream != nullptr && c->prof_level < 2) {
+    if (c->expand_exec == nullptr) {
+      hipGraph_t graph = nullptr;
+      HIPCHK(c, hipStreamBeginCapture(c->stream, hipStreamCaptureModeThreadLocal));
+      rc = expand_all(c->t_base, 0, c->seq_draft - 1);
+      hipError_t e = hipStreamEndCapture(c->stream, &graph);
+      if (rc) { if (graph) (void)hipGraphDestroy(graph); return rc; }
+      if (e != hipSuccess) return fail(c, SPEC_EHIP, "graph capture (draft): %s", hipGetErrorString(e));
+      e = hipGraphInstantiate(&c->expand_exec, graph, nullptr, nullptr, 0);
+      (void)hipGraphDestroy(graph);
+      if (e != hipSuccess) { c->expand_exec = nullptr; return fail(c, SPEC_EHIP, "graph instantiate (draft): %s", hipGetErrorString(e)); }
+    }
+    HIPCHK(c, hipGraphLaunch(c->expand_exec, c->stream));
+  } else {
+    rc = expand_all(nullptr, c->n, 0);
     if (rc) return rc;
-    rc = lm_head(c, c->gfeat, K, c->dlogits);
-    if (rc) return rc;
-    HIPCHK(c, launch_rows_topk_logprob(c->dlogits, K, g.vocab, K, c->sc_val, c->sc_idx, c->sc_stat, c->top_tok, c->top_lp, c->stream));
-    HIPCHK(c, launch_pool_expand(c->ds, c->top_tok, c->top_lp, K, t, c->n, t < D ? 1 : 0, c->stream));
   }
-  HIPCHK(c, launch_rerank(c->ds, g.tree_total, c->root_tok, c->t_n, c->t_tok, c->t_par, c->t_dep, c->t_sc, c->stream));
   c->gemm_bucket = 0;
   HIPCHK(c, hipMemcpyAsync(&c->stage->tree_n, c->t_n, offsetof(HostStage, pos), hipMemcpyDeviceToHost, c->stream));
   phase_end(c, 0);
@@ -667,7 +702,7 @@ int spec_accept(spec_ctx *c, const spec_tree *tree, int32_t *out_tokens, int32_t
     HIPCHK(c, launch_accept_greedy(c->row_argmax, c->t_tok, c->t_par, N, c->acc, c->stream));
   }
   HIPCHK(c, launch_commit(g.dtype, c->acc, c->kv_t, c->t_layer_stride, c->t_kv_stride, g.n_layers, g.n_kv_heads * g.head_dim,
-                          c->n, c->feats, g.d_model, c->pend_feat, c->pend_tok, c->root_tok, c->stream));
+                          c->n, c->feats, g.d_model, c->pend_feat, c->pend_tok, c->root_tok, c->t_base, c->stream));
   HIPCHK(c, hipMemcpyAsync(&c->stage->acc, c->acc, sizeof(AcceptResult), hipMemcpyDeviceToHost, c->stream));
   phase_end(c, 2);
   int rc = sync(c);

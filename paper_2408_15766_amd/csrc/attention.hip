@@ -29,8 +29,8 @@
 //    only, so a row is computed by the same instructions over the same key groups whether it is
 //    alone or part of a tree.
 //
-// Parts (fixed absolute boundaries, kAttnPart positions) are merged per row in ascending order by
-// attn_combine_kernel, the tail last.
+// Parts (fixed absolute boundaries, kAttnPart positions) are merged per row in ascending order, the tail
+// last: by the tail wave itself in the hybrid path, by attn_combine_kernel in the pure vector path.
 #include "common.h"
 #include "kernels.h"
 
@@ -72,7 +72,6 @@ __global__ __launch_bounds__(64) void attn_part_kernel(AttnArgs a) {
   const int k_lo = a.tail_only ? bulk_end(p) : part * kAttnPart;
   const int k_hi = a.tail_only ? p + 1 : min(p + 1, k_lo + kAttnPart);
   if (k_lo >= k_hi) return;
-  const int part_slot = a.tail_only ? a.max_parts - 1 : part;
 
   const float *qrow = (const float *)a.q + ((size_t)i * a.hq + (size_t)hk * G) * HD;   // queries are fp32
   for (int e = lane; e < G * HD; e += 64) qs[e / HD][e % HD] = qrow[e];
@@ -152,25 +151,52 @@ __global__ __launch_bounds__(64) void attn_part_kernel(AttnArgs a) {
         }
     }
   }
+  if (a.tail_only) {
+    // Hybrid mode: the bulk parts of this row are complete (the bulk kernel ran before this one), so the
+    // tail wave merges them with its own result in ascending part order, the tail last, and writes the
+    // final output; no separate merge pass.
+    const int n_parts = (bulk_end(p) + kAttnPart - 1) / kAttnPart;
+#pragma unroll
+    for (int gh = 0; gh < G; gh++) {
+      const float *src = a.part + ((size_t)i * a.hq + hk * G + gh) * a.max_parts * (HD + 2);
+      float m = m_run[gh];
+      for (int t = 0; t < n_parts; t++) m = fmaxf(m, src[(size_t)t * (HD + 2)]);
+      float l = 0.f, acc[DPL];
+#pragma unroll
+      for (int dd = 0; dd < DPL; dd++) acc[dd] = 0.f;
+      for (int t = 0; t < n_parts; t++) {
+        const float *sp = src + (size_t)t * (HD + 2);
+        const float w = __expf(sp[0] - m);
+        l += sp[1] * w;
+#pragma unroll
+        for (int dd = 0; dd < DPL; dd++) acc[dd] += sp[2 + lane * DPL + dd] * w;
+      }
+      const float w = __expf(m_run[gh] - m);
+      l += l_run[gh] * w;
+      T *dst = (T *)a.out + ((size_t)i * a.hq + hk * G + gh) * HD + lane * DPL;
+#pragma unroll
+      for (int dd = 0; dd < DPL; dd++) dst[dd] = from_f32<T>((acc[dd] + o[gh][dd] * w) / l);
+    }
+    return;
+  }
 #pragma unroll
   for (int gh = 0; gh < G; gh++) {
-    float *dst = a.part + (((size_t)i * a.hq + hk * G + gh) * a.max_parts + part_slot) * (HD + 2);
+    float *dst = a.part + (((size_t)i * a.hq + hk * G + gh) * a.max_parts + part) * (HD + 2);
     if (lane == 0) { dst[0] = m_run[gh]; dst[1] = l_run[gh]; }
 #pragma unroll
     for (int dd = 0; dd < DPL; dd++) dst[2 + lane * DPL + dd] = o[gh][dd];
   }
 }
 
-// grid (rows, hq); block HD threads.  Merges the row's parts in ascending order.
+// grid (rows, hq); block HD threads.  Merges the row's parts in ascending order (vector path over the
+// whole range; in hybrid mode the tail wave does the merge itself).
 template <typename T, int HD>
 __global__ void attn_combine_kernel(AttnArgs a) {
   const int i = blockIdx.x, h = blockIdx.y, d = threadIdx.x;
   const int p = (a.base_ptr ? *a.base_ptr : a.base) + a.depth[i];
-  // full mode: parts 0 .. p/kAttnPart; hybrid mode: the bulk parts that hold keys of this row, then the tail slot
-  const int n_parts = a.tail_only ? (bulk_end(p) + kAttnPart - 1) / kAttnPart : p / kAttnPart + 1;
+  const int n_parts = p / kAttnPart + 1;
   const float *src = a.part + ((size_t)i * a.hq + h) * a.max_parts * (HD + 2);
-  const float *tail = src + (size_t)(a.max_parts - 1) * (HD + 2);
-  float m = a.tail_only ? tail[0] : -INFINITY;
+  float m = -INFINITY;
   for (int t = 0; t < n_parts; t++) m = fmaxf(m, src[(size_t)t * (HD + 2)]);
   float l = 0.f, o = 0.f;
   for (int t = 0; t < n_parts; t++) {
@@ -178,11 +204,6 @@ __global__ void attn_combine_kernel(AttnArgs a) {
     const float w = __expf(s[0] - m);
     l += s[1] * w;
     o += s[2 + d] * w;
-  }
-  if (a.tail_only) {
-    const float w = __expf(tail[0] - m);
-    l += tail[1] * w;
-    o += tail[2 + d] * w;
   }
   ((T *)a.out)[((size_t)i * a.hq + h) * HD + d] = from_f32<T>(o / l);
 }
@@ -362,7 +383,7 @@ static hipError_t launch_thg(AttnArgs a, int max_pos, hipStream_t st) {
     a.tail_only = 1;
     a.bulk_blocks = bulk_end(max_pos) / 32;
     const int n_bulk_parts = (a.bulk_blocks + kBulkBlocksPerPart - 1) / kBulkBlocksPerPart;
-    if (n_bulk_parts + 1 > a.max_parts) return hipErrorInvalidValue;
+    if (n_bulk_parts > a.max_parts) return hipErrorInvalidValue;
     if (n_bulk_parts > 0) {
       const int qblocks = (a.rows * G + 31) / 32;
       if (qblocks <= 1) e = launch_bulk<HD, G, 1>(a, n_bulk_parts, 1, st);
@@ -372,6 +393,7 @@ static hipError_t launch_thg(AttnArgs a, int max_pos, hipStream_t st) {
       if (e != hipSuccess) return e;
     }
     hipLaunchKernelGGL((attn_part_kernel<T, HD, G>), dim3(a.rows, a.hkv, 1), dim3(64), 0, st, a);
+    return hipGetLastError();
   } else {
     a.tail_only = 0;
     a.bulk_blocks = 0;

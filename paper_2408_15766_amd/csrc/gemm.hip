@@ -89,10 +89,14 @@ __global__ __launch_bounds__(kGemmThreads, TB <= 2 ? 2 : 1) void gemm_stream_ker
   // argument struct: that would push it to private memory).
   // A wave past the last block recomputes the last block and stores nothing, so that every wave
   // runs the same branch-free loop and the same barriers.
-  const int blk_raw = blockIdx.x * kGemmWaves + wave;
+  // SwiGLU mode pairs blocks instead: waves 0,1 take gate blocks 2x, 2x+1 and waves 2,3 the same up blocks.
+  const bool swiglu = a.act != nullptr;
+  const int e0 = a.seg_blocks[0], e1 = e0 + (a.nseg > 1 ? a.seg_blocks[1] : 0);
+  const int half_waves = kGemmWaves / 2;
+  const int pair_raw = blockIdx.x * half_waves + (wave % half_waves);
+  const int blk_raw = swiglu ? (pair_raw < e0 ? (wave / half_waves) * e0 + pair_raw : a.total_blocks) : blockIdx.x * kGemmWaves + wave;
   const bool active = blk_raw < a.total_blocks;
   const int blk = active ? blk_raw : a.total_blocks - 1;
-  const int e0 = a.seg_blocks[0], e1 = e0 + (a.nseg > 1 ? a.seg_blocks[1] : 0);
   const int seg = blk < e0 ? 0 : (blk < e1 ? 1 : 2);
   const int b0 = seg == 0 ? 0 : (seg == 1 ? e0 : e1);
   const int seg_rows = seg == 0 ? a.seg_rows[0] : (seg == 1 ? a.seg_rows[1] : a.seg_rows[2]);
@@ -208,6 +212,31 @@ __global__ __launch_bounds__(kGemmThreads, TB <= 2 ? 2 : 1) void gemm_stream_ker
     slab(I2{}, std::false_type{}, s + 2);
   }
 
+  if (swiglu) {
+    // the up waves hand their tiles to the gate waves through LDS (the X slabs are no longer needed)
+    float *xch = (float *)lds;                                // [half_waves][64 lanes][TB*16]
+    __syncthreads();
+    if (wave >= half_waves) {
+      float *dst = xch + ((size_t)(wave - half_waves) * 64 + lane) * (TB * 16);
+#pragma unroll
+      for (int t = 0; t < TB; t++)
+#pragma unroll
+        for (int v = 0; v < 16; v++) dst[t * 16 + v] = acc[t][v];
+    }
+    __syncthreads();
+    if (wave >= half_waves || !active || row >= seg_rows) return;
+    const float *src = xch + ((size_t)wave * 64 + lane) * (TB * 16);
+    T *act = (T *)a.act + row;
+#pragma unroll
+    for (int t = 0; t < TB; t++)
+#pragma unroll
+      for (int v = 0; v < 16; v++) {
+        const int i = t * 32 + 8 * (v >> 2) + 4 * g + (v & 3);
+        const float gv = acc[t][v], uv = src[t * 16 + v];
+        if (i < a.m) act[(size_t)i * seg_rows] = from_f32<T>(gv / (1.0f + expf(-gv)) * uv);
+      }
+    return;
+  }
   if (!active || row >= seg_rows) return;
   float *out = a.part + ((size_t)blockIdx.y * a.m_pad) * a.ldp + seg_col0 + row;
 #pragma unroll
@@ -283,6 +312,10 @@ template <typename T>
 static hipError_t launch_t(const GemmArgs &a, hipStream_t st) {
   const int tb = (a.m + 31) / 32;
   dim3 grid((a.total_blocks + kGemmWaves - 1) / kGemmWaves, a.n_split);
+  if (a.act != nullptr) {                                      // SwiGLU mode: one workgroup per two gate/up block pairs
+    if (a.nseg != 2 || a.n_split != 1 || a.seg_rows[0] != a.seg_rows[1] || (kGemmWaves & 1)) return hipErrorInvalidValue;
+    grid = dim3((a.seg_blocks[0] + kGemmWaves / 2 - 1) / (kGemmWaves / 2), 1);
+  }
   const size_t lds = (size_t)2 * tb * 32 * kSlabStride;
   if (lds > 160 * 1024) return hipErrorInvalidValue;
   switch (tb) {

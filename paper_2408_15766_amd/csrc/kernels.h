@@ -24,6 +24,10 @@ struct GemmArgs {
   int nseg, total_blocks;
   float *part;  int ldp;  int m_pad;    // partial sums [n_split][m_pad][ldp], fp32
   int n_split;                          // K is cut into n_split ranges of whole slabs, balanced to one slab
+  // SwiGLU mode (act != nullptr): exactly two segments, gate and up, of seg_rows[0] rows each, n_split = 1.
+  // A workgroup then owns two gate blocks and the SAME two up blocks and writes
+  // act[i][c] = silu(gate) * up in the storage type instead of partial sums.
+  void *act;
 };
 hipError_t launch_gemm(int dtype, const GemmArgs &a, hipStream_t st);
 hipError_t gemm_init();                 // one-time kernel attributes; call outside any stream capture
@@ -99,13 +103,14 @@ struct DraftState {
   int *front_slot;                                       // [K] cache slot the row's key/value go to
   int *front_pos;                                        // [K] rotary position
 };
+// n_draft (device int): committed draft-cache entries = committed tokens; scratch slots start there.
 // After the root step: pool <- top-k of the root row; frontier <- those k nodes.
 hipError_t launch_pool_init(const DraftState &s, const int *top_tok, const float *top_lp, int k, int root_row,
-                            int n_draft, hipStream_t st);
+                            const int *n_draft, hipStream_t st);
 // After expansion step t (frontier rows = k nodes of depth t-1): append k*k children; if `select_next`,
 // choose the k best children as the next frontier and derive its attention tables.
 hipError_t launch_pool_expand(const DraftState &s, const int *top_tok, const float *top_lp, int k, int step,
-                              int n_draft, int select_next, hipStream_t st);
+                              const int *n_draft, int select_next, hipStream_t st);
 // Rerank: best (total-1) pool entries by score (ties: lower pool index), kept in pool order.
 // tree_* arrays have room for `total` nodes; node 0 = root.
 hipError_t launch_rerank(const DraftState &s, int total, const int *root_tok, int *tree_n, int *tree_tok, int *tree_par,
@@ -125,9 +130,10 @@ hipError_t launch_accept_sample(const float *logits, int vocab, const float2 *st
 hipError_t launch_sample_row(const float *logits, int vocab, float temp, uint64_t seed, uint32_t cycle, uint32_t node,
                              int *out, hipStream_t st);
 // Commit: in every layer move key/value of accepted node d from slot n + node[d] to slot n + d; gather
-// the features of root + accepted rows and the tokens for the next draft root step; *root_tok <- bonus.
+// the features of root + accepted rows and the tokens for the next draft root step; *root_tok <- bonus;
+// *n_committed (device) += 1 + accepted.
 hipError_t launch_commit(int dtype, const AcceptResult *res, void *kv_base, size_t layer_stride, size_t kv_stride,
                          int n_layers, int row_elems, int n, const void *feat, int d, void *pend_feat, int *pend_tok,
-                         int *root_tok, hipStream_t st);
+                         int *root_tok, int *n_committed, hipStream_t st);
 
 }  // namespace spec

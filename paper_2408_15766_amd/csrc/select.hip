@@ -164,8 +164,10 @@ hipError_t launch_rows_topk_logprob(const float *logits, int rows, int vocab, in
 
 // ---- candidate pool ------------------------------------------------------------------------
 // top_tok / top_lp rows have stride kMaxTopK.
-__global__ void pool_init_kernel(DraftState s, const int *top_tok, const float *top_lp, int k, int root_row, int n_draft) {
+__global__ void pool_init_kernel(DraftState s, const int *top_tok, const float *top_lp, int k, int root_row,
+                                 const int *n_draft_ptr) {
   const int r = threadIdx.x;
+  const int n_draft = *n_draft_ptr;
   if (r < k) {
     s.pool_tok[r] = top_tok[r]; s.pool_par[r] = -1; s.pool_dep[r] = 1; s.pool_sc[r] = top_lp[r];
     s.front_pool[r] = r; s.front_tok[r] = top_tok[r]; s.front_src[r] = root_row; s.front_depth[r] = 0;
@@ -176,7 +178,7 @@ __global__ void pool_init_kernel(DraftState s, const int *top_tok, const float *
   if (r == 0) *s.n_pool = k;
 }
 hipError_t launch_pool_init(const DraftState &s, const int *top_tok, const float *top_lp, int k, int root_row,
-                            int n_draft, hipStream_t st) {
+                            const int *n_draft, hipStream_t st) {
   if (k < 1 || k > kMaxTopK) return hipErrorInvalidValue;
   hipLaunchKernelGGL(pool_init_kernel, dim3(1), dim3(64), 0, st, s, top_tok, top_lp, k, root_row, n_draft);
   return hipGetLastError();
@@ -184,11 +186,12 @@ hipError_t launch_pool_init(const DraftState &s, const int *top_tok, const float
 
 // `step` t in 2..D: the k frontier rows are nodes of depth t-1; their children have depth t.
 __global__ __launch_bounds__(kSelThreads) void pool_expand_kernel(DraftState s, const int *top_tok, const float *top_lp,
-                                                                  int k, int step, int n_draft, int select_next) {
+                                                                  int k, int step, const int *n_draft_ptr, int select_next) {
   __shared__ float sc[kMaxTopK * kMaxTopK];
   __shared__ int old_anc[kMaxTopK * kAncStride];
   __shared__ int old_pool[kMaxTopK];
   const int t = threadIdx.x, kk = k * k;
+  const int n_draft = *n_draft_ptr;
   const int base = *s.n_pool;
   if (t < k) old_pool[t] = s.front_pool[t];
   for (int e = t; e < k * kAncStride; e += kSelThreads) old_anc[e] = s.front_anc[e];
@@ -215,7 +218,7 @@ __global__ __launch_bounds__(kSelThreads) void pool_expand_kernel(DraftState s, 
   s.front_pos[rank] = n_draft + 1 + (step - 1);
 }
 hipError_t launch_pool_expand(const DraftState &s, const int *top_tok, const float *top_lp, int k, int step,
-                              int n_draft, int select_next, hipStream_t st) {
+                              const int *n_draft, int select_next, hipStream_t st) {
   if (k < 1 || k > kMaxTopK || step < 2 || step > kMaxDepth) return hipErrorInvalidValue;
   hipLaunchKernelGGL(pool_expand_kernel, dim3(1), dim3(kSelThreads), 0, st, s, top_tok, top_lp, k, step, n_draft, select_next);
   return hipGetLastError();
@@ -413,8 +416,9 @@ __global__ __launch_bounds__(kSelThreads) void compact_kv_kernel(const AcceptRes
 // Features of root + accepted rows and the matching tokens for the next draft root step.
 template <typename T>
 __global__ __launch_bounds__(kSelThreads) void handoff_kernel(const AcceptResult *res, const T *feat, int d, T *pend_feat,
-                                                              int *pend_tok, int *root_tok) {
+                                                              int *pend_tok, int *root_tok, int *n_committed) {
   const int r = blockIdx.x, m = res->n_acc;
+  if (r == 0 && threadIdx.x == 0) *n_committed += 1 + m;      // root + accepted tokens are now in the cache
   if (r > m) return;
   const T *src = feat + (size_t)res->node[r] * d;
   T *dst = pend_feat + (size_t)r * d;
@@ -426,7 +430,7 @@ __global__ __launch_bounds__(kSelThreads) void handoff_kernel(const AcceptResult
 }
 hipError_t launch_commit(int dtype, const AcceptResult *res, void *kv_base, size_t layer_stride, size_t kv_stride,
                          int n_layers, int row_elems, int n, const void *feat, int d, void *pend_feat, int *pend_tok,
-                         int *root_tok, hipStream_t st) {
+                         int *root_tok, int *n_committed, hipStream_t st) {
   const size_t esz = dtype == 1 ? 2 : 4;
   const int row_bytes = (int)(row_elems * esz);
   if (row_bytes % 16 != 0 || n_layers < 1) return hipErrorInvalidValue;
@@ -438,10 +442,10 @@ hipError_t launch_commit(int dtype, const AcceptResult *res, void *kv_base, size
   if (e != hipSuccess) return e;
   if (dtype == 1)
     hipLaunchKernelGGL(handoff_kernel<bf16_t>, dim3(kMaxDepth + 1), dim3(kSelThreads), 0, st, res, (const bf16_t *)feat, d,
-                       (bf16_t *)pend_feat, pend_tok, root_tok);
+                       (bf16_t *)pend_feat, pend_tok, root_tok, n_committed);
   else
     hipLaunchKernelGGL(handoff_kernel<float>, dim3(kMaxDepth + 1), dim3(kSelThreads), 0, st, res, (const float *)feat, d,
-                       (float *)pend_feat, pend_tok, root_tok);
+                       (float *)pend_feat, pend_tok, root_tok, n_committed);
   return hipGetLastError();
 }
 
