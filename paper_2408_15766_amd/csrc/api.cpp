@@ -71,7 +71,8 @@ struct spec_ctx {
   float *sc_val = nullptr, *top_lp = nullptr;
   int *sc_idx = nullptr, *top_tok = nullptr;
   int *d_prompt = nullptr, *d_pos = nullptr, *d_slot = nullptr, *d_depth = nullptr;
-  int *pend_tok = nullptr, *root_tok = nullptr, *row_argmax = nullptr;
+  int *pend_tok = nullptr, *root_tok = nullptr, *amax_idx = nullptr;
+  float *amax_val = nullptr;
   // verify tree on the device: packed exactly like the head of HostStage (tree_n .. anc)
   int *t_n = nullptr, *t_base = nullptr, *t_tok = nullptr, *t_par = nullptr, *t_dep = nullptr, *t_pos = nullptr, *t_slot = nullptr, *t_anc = nullptr;
   float *t_sc = nullptr;
@@ -210,7 +211,8 @@ size_t layout(const spec_config &c, spec_ctx *x, char *base) {
   TAKE(d_depth, int *, (size_t)m_max * 4)
   TAKE(pend_tok, int *, (size_t)(kMaxDepth + 1) * 4)
   TAKE(root_tok, int *, 256)
-  TAKE(row_argmax, int *, (size_t)kMaxNodes * 4)
+  TAKE(amax_val, float *, (size_t)kMaxNodes * argmax_slices(c.vocab) * 4)
+  TAKE(amax_idx, int *, (size_t)kMaxNodes * argmax_slices(c.vocab) * 4)
   // verify tree: one contiguous block mirroring the head of HostStage, so one copy moves it
   {
     size_t o_ = L.take(offsetof(HostStage, acc));
@@ -513,7 +515,7 @@ int spec_prefill(spec_ctx *c, const int32_t *prompt, int32_t n_prompt, int32_t *
       if (g.temperature > 0.f)
         HIPCHK(c, launch_sample_row(c->logits, g.vocab, g.temperature, g.seed, 0, 0, c->root_tok, c->stream));
       else
-        HIPCHK(c, launch_rows_argmax(c->logits, 1, g.vocab, c->root_tok, c->stream));
+        HIPCHK(c, launch_rows_argmax(c->logits, 1, g.vocab, c->amax_val, c->amax_idx, c->root_tok, c->stream));
       // pending pair for the first draft root step: (feature of the last prompt position, first token)
       HIPCHK(c, hipMemcpyAsync(c->pend_feat, (const char *)c->feats + (size_t)(m - 1) * g.d_model * c->esz,
                                (size_t)g.d_model * c->esz, hipMemcpyDeviceToDevice, c->stream));
@@ -698,8 +700,8 @@ int spec_accept(spec_ctx *c, const spec_tree *tree, int32_t *out_tokens, int32_t
     HIPCHK(c, launch_rows_softmax_stats(c->logits, N, g.vocab, g.temperature, c->stats, c->stream));
     HIPCHK(c, launch_accept_sample(c->logits, g.vocab, c->stats, g.temperature, c->t_tok, c->t_par, N, g.seed, c->cycle, c->acc, c->stream));
   } else {
-    HIPCHK(c, launch_rows_argmax(c->logits, N, g.vocab, c->row_argmax, c->stream));
-    HIPCHK(c, launch_accept_greedy(c->row_argmax, c->t_tok, c->t_par, N, c->acc, c->stream));
+    HIPCHK(c, launch_rows_argmax(c->logits, N, g.vocab, c->amax_val, c->amax_idx, nullptr, c->stream));
+    HIPCHK(c, launch_accept_greedy(c->amax_val, c->amax_idx, argmax_slices(g.vocab), c->t_tok, c->t_par, N, c->acc, c->stream));
   }
   HIPCHK(c, launch_commit(g.dtype, c->acc, c->kv_t, c->t_layer_stride, c->t_kv_stride, g.n_layers, g.n_kv_heads * g.head_dim,
                           c->n, c->feats, g.d_model, c->pend_feat, c->pend_tok, c->root_tok, c->t_base, c->stream));

@@ -18,7 +18,7 @@
 //    LDS key by key in position order.  Used for fp32 storage, and for the TAIL
 //    of every row in bf16 storage.
 //
-//  * matrix-core path (attn_bulk_kernel, bf16 storage): the BULK of a row's keys, positions
+//  * matrix-core path (bulk workgroups of attn_hybrid_kernel, bf16 storage): the BULK of a row's keys, positions
 //    [0, A(p)) with A(p) = 32 * floor(max(p - kMaxDepth, 0) / 32), lies in the committed cache
 //    for every row of a tree (depth <= kMaxDepth), is the same key set for spec and plain decoding,
 //    and is shared by all rows, so it runs as dense 32-key blocks on the MFMA units: S^T = K Q^T
@@ -30,7 +30,8 @@
 //    alone or part of a tree.
 //
 // Parts (fixed absolute boundaries, kAttnPart positions) are merged per row in ascending order, the tail
-// last: by the tail wave itself in the hybrid path, by attn_combine_kernel in the pure vector path.
+// last, by attn_combine_kernel.  In the hybrid path the bulk and the tail are independent and run in ONE
+// launch (different workgroups), so the chain per layer is two dependent kernels.
 #include "common.h"
 #include "kernels.h"
 
@@ -58,14 +59,29 @@ template <> struct Chunk<bf16_t> {
 // End of the bulk region of a row at position p (a multiple of 32, <= p - kMaxDepth): see the header.
 __device__ __host__ __forceinline__ int bulk_end(int p) { return p > kMaxDepth ? ((p - kMaxDepth) / 32) * 32 : 0; }
 
-template <typename T, int HD, int G>
-__global__ __launch_bounds__(64) void attn_part_kernel(AttnArgs a) {
+// Orders this wavefront's LDS writes before its later LDS reads of other lanes' data.  The LDS executes
+// one wavefront's operations in issue order, so only the compiler has to be kept from reordering them.
+__device__ __forceinline__ void wave_lds_sync() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// One wavefront: row i, kv head hk, part `part` (full mode) or the tail range (tail mode).  `qs` and `vs`
+// are this wavefront's own LDS areas ([G][HD] floats and 64 staged value rows); no workgroup barrier is
+// used, so wavefronts of one workgroup may work on different items.  `store` = false discards the result.
+template <typename T> struct PartLds {
+  static constexpr int vrow(int hd) { return hd * (int)sizeof(T) + 16; }   // +16: conflict-free row writes
+};
+// VR = staged value rows the caller provides: 64 in general; the tail range never exceeds 32 + kMaxDepth keys.
+constexpr int kTailRows = 48;
+static_assert(32 + kMaxDepth <= kTailRows && kTailRows % 8 == 0, "tail staging area too small");
+template <typename T, int HD, int G, int VR>
+__device__ __forceinline__ void attn_part_body(const AttnArgs &a, int i, int hk, int part, int lane, float (*qs)[HD],
+                                               unsigned char *vs, bool store) {
   constexpr int EPL = Chunk<T>::kEpl;
   constexpr int DPL = HD / 64;                       // output dims per lane (contiguous)
-  constexpr int VROW = HD * (int)sizeof(T) + 16;     // LDS bytes per staged value row (+16: conflict-free row writes)
-  __shared__ __attribute__((aligned(16))) float qs[G][HD];
-  __shared__ __attribute__((aligned(16))) unsigned char vs[64 * VROW];
-  const int i = blockIdx.x, hk = blockIdx.y, part = blockIdx.z, lane = threadIdx.x;
+  constexpr int VROW = PartLds<T>::vrow(HD);         // LDS bytes per staged value row
   const int base = a.base_ptr ? *a.base_ptr : a.base;  // device-resident when the launch is replayed from a graph
   const int p = base + a.depth[i];
   // full mode: part `part` of the whole range [0, p]; tail mode: the single range [A(p), p]
@@ -101,7 +117,7 @@ __global__ __launch_bounds__(64) void attn_part_kernel(AttnArgs a) {
     for (int dc = 0; dc < HD / EPL; dc++) kc[dc] = *(const u32x4_t *)(kptr + dc * EPL);
 #pragma unroll
     for (int dc = 0; dc < HD / EPL; dc++) vc[dc] = *(const u32x4_t *)(vptr + dc * EPL);
-    __syncthreads();                                   // qs written (first pass) / previous block's vs reads done
+    wave_lds_sync();                                   // qs written (first pass) / previous block's vs reads done
     float s[G];
 #pragma unroll
     for (int gh = 0; gh < G; gh++) s[gh] = 0.f;
@@ -114,9 +130,11 @@ __global__ __launch_bounds__(64) void attn_part_kernel(AttnArgs a) {
 #pragma unroll
         for (int e = 0; e < EPL; e++) s[gh] = fmaf(qs[gh][dc * EPL + e], kf[e], s[gh]);
     }
-    // stage the value rows: row `lane` of vs
+    // stage the value rows: row `lane` of vs (lanes past VR never hold a key)
+    if (VR == 64 || lane < VR) {
 #pragma unroll
-    for (int dc = 0; dc < HD / EPL; dc++) *(u32x4_t *)(vs + lane * VROW + dc * 16) = vc[dc];
+      for (int dc = 0; dc < HD / EPL; dc++) *(u32x4_t *)(vs + lane * VROW + dc * 16) = vc[dc];
+    }
     float pk[G];
 #pragma unroll
     for (int gh = 0; gh < G; gh++) {
@@ -129,7 +147,7 @@ __global__ __launch_bounds__(64) void attn_part_kernel(AttnArgs a) {
       for (int dd = 0; dd < DPL; dd++) o[gh][dd] *= corr;
       m_run[gh] = m_new;
     }
-    __syncthreads();                                   // value rows staged
+    wave_lds_sync();                                   // value rows staged
     // lane = output dims lane*DPL ..: accumulate key by key in position order
     // Eight keys per step so that the LDS reads of a step are in flight together.  Lanes past the last
     // key hold weight 0 and a valid finite value row (slot 0), so rounding a step up to eight adds zeros.
@@ -151,56 +169,40 @@ __global__ __launch_bounds__(64) void attn_part_kernel(AttnArgs a) {
         }
     }
   }
-  if (a.tail_only) {
-    // Hybrid mode: the bulk parts of this row are complete (the bulk kernel ran before this one), so the
-    // tail wave merges them with its own result in ascending part order, the tail last, and writes the
-    // final output; no separate merge pass.
-    const int n_parts = (bulk_end(p) + kAttnPart - 1) / kAttnPart;
-#pragma unroll
-    for (int gh = 0; gh < G; gh++) {
-      const float *src = a.part + ((size_t)i * a.hq + hk * G + gh) * a.max_parts * (HD + 2);
-      float m = m_run[gh];
-      for (int t = 0; t < n_parts; t++) m = fmaxf(m, src[(size_t)t * (HD + 2)]);
-      float l = 0.f, acc[DPL];
-#pragma unroll
-      for (int dd = 0; dd < DPL; dd++) acc[dd] = 0.f;
-      for (int t = 0; t < n_parts; t++) {
-        const float *sp = src + (size_t)t * (HD + 2);
-        const float w = __expf(sp[0] - m);
-        l += sp[1] * w;
-#pragma unroll
-        for (int dd = 0; dd < DPL; dd++) acc[dd] += sp[2 + lane * DPL + dd] * w;
-      }
-      const float w = __expf(m_run[gh] - m);
-      l += l_run[gh] * w;
-      T *dst = (T *)a.out + ((size_t)i * a.hq + hk * G + gh) * HD + lane * DPL;
-#pragma unroll
-      for (int dd = 0; dd < DPL; dd++) dst[dd] = from_f32<T>((acc[dd] + o[gh][dd] * w) / l);
-    }
-    return;
-  }
+  if (!store) return;
+  const int part_slot = a.tail_only ? a.max_parts - 1 : part;   // the tail goes to the last slot
 #pragma unroll
   for (int gh = 0; gh < G; gh++) {
-    float *dst = a.part + (((size_t)i * a.hq + hk * G + gh) * a.max_parts + part) * (HD + 2);
+    float *dst = a.part + (((size_t)i * a.hq + hk * G + gh) * a.max_parts + part_slot) * (HD + 2);
     if (lane == 0) { dst[0] = m_run[gh]; dst[1] = l_run[gh]; }
 #pragma unroll
     for (int dd = 0; dd < DPL; dd++) dst[2 + lane * DPL + dd] = o[gh][dd];
   }
 }
 
-// grid (rows, hq); block HD threads.  Merges the row's parts in ascending order (vector path over the
-// whole range; in hybrid mode the tail wave does the merge itself).
+// grid (rows, kv heads, parts); one wavefront per workgroup.
+template <typename T, int HD, int G>
+__global__ __launch_bounds__(64) void attn_part_kernel(AttnArgs a) {
+  __shared__ __attribute__((aligned(16))) float qs[G][HD];
+  __shared__ __attribute__((aligned(16))) unsigned char vs[64 * PartLds<T>::vrow(HD)];
+  attn_part_body<T, HD, G, 64>(a, blockIdx.x, blockIdx.y, blockIdx.z, threadIdx.x, qs, vs, true);
+}
+
+// grid (rows, hq); block HD threads.  Merges the row's parts in ascending order; in hybrid mode these are
+// the bulk parts followed by the tail (kept in the last slot).
 template <typename T, int HD>
 __global__ void attn_combine_kernel(AttnArgs a) {
   const int i = blockIdx.x, h = blockIdx.y, d = threadIdx.x;
   const int p = (a.base_ptr ? *a.base_ptr : a.base) + a.depth[i];
-  const int n_parts = p / kAttnPart + 1;
+  const int n_front = a.tail_only ? (bulk_end(p) + kAttnPart - 1) / kAttnPart : p / kAttnPart + 1;
+  const int n_parts = n_front + (a.tail_only ? 1 : 0);
   const float *src = a.part + ((size_t)i * a.hq + h) * a.max_parts * (HD + 2);
+  auto slot = [&](int t) { return (size_t)(t < n_front ? t : a.max_parts - 1) * (HD + 2); };
   float m = -INFINITY;
-  for (int t = 0; t < n_parts; t++) m = fmaxf(m, src[(size_t)t * (HD + 2)]);
+  for (int t = 0; t < n_parts; t++) m = fmaxf(m, src[slot(t)]);
   float l = 0.f, o = 0.f;
   for (int t = 0; t < n_parts; t++) {
-    const float *s = src + (size_t)t * (HD + 2);
+    const float *s = src + slot(t);
     const float w = __expf(s[0] - m);
     l += s[1] * w;
     o += s[2 + d] * w;
@@ -230,20 +232,42 @@ __device__ __forceinline__ f32x16_t mfma_bf16(const u32x4_t &a, const u32x4_t &b
 
 constexpr int kBulkBlocksPerPart = kAttnPart / 32;
 
-// grid (parts, kv heads, groups of NW query blocks); block NW waves.  Wave w owns 32 "query rows"
-// (row i, head gh of the kv group), r = qblock*32 + lane%32, i = r / G, gh = r % G.
+// One launch covers both regions of the hybrid path.  Workgroups [0, n_bulk) (n_bulk = bulk_parts * kv heads
+// * q_groups, part fastest) run the matrix-core bulk: NW waves, wave w owns 32 "query rows" (row i, head gh
+// of the kv group), r = (qgroup*NW + w)*32 + lane%32, i = r / G, gh = r % G.  The remaining workgroups run
+// the vector tail, one (row, kv head) item per wavefront on the first kTailWaves wavefronts, and leave it in
+// the last part slot.  The two kinds of work are independent; attn_combine_kernel merges them afterwards.
+template <int NW> struct TailWaves { static constexpr int value = NW < 2 ? 1 : 2; };
 template <int HD, int G, int NW>
-__global__ __launch_bounds__(NW * 64) void attn_bulk_kernel(AttnArgs a) {
+__global__ __launch_bounds__(NW * 64) void attn_hybrid_kernel(AttnArgs a) {
   constexpr int DB = HD / 32;                 // 32-dim blocks of the output
   constexpr int KK = HD / 16;                 // MFMA steps of q.k
   constexpr int KSTR = HD * 2 + 16;           // LDS bytes per key row (+16: conflict-free b128 reads)
   constexpr int VSTR = 32 * 2 + 8;            // LDS bytes per dim row of V^T (+8: conflict-free b64 reads)
   constexpr int NT = NW * 64;
   constexpr int PIECES = (32 * HD * 2 / 16 + NT - 1) / NT;   // 16-byte pieces of one K (or V) block per thread
-  __shared__ __attribute__((aligned(16))) unsigned char k_lds[32 * KSTR];
-  __shared__ __attribute__((aligned(16))) unsigned char vt_lds[HD * VSTR];
+  constexpr int kTailWaves = TailWaves<NW>::value;
+  constexpr int kTailQ = G * HD * 4;                                         // a tail wavefront's query area
+  constexpr int kTailWave = kTailQ + kTailRows * PartLds<bf16_t>::vrow(HD);  // ... plus its staged value rows
+  constexpr int kBulkLds = 32 * KSTR + HD * VSTR;
+  constexpr int kLds = kBulkLds > kTailWaves * kTailWave ? kBulkLds : kTailWaves * kTailWave;
+  __shared__ __attribute__((aligned(16))) unsigned char lds[kLds];
 
-  const int part = blockIdx.x, hk = blockIdx.y;
+  const int n_bulk = a.bulk_parts * a.hkv * a.q_groups;
+  if ((int)blockIdx.x >= n_bulk) {
+    const int w = threadIdx.x >> 6;
+    if (w >= kTailWaves) return;
+    int item = ((int)blockIdx.x - n_bulk) * kTailWaves + w;
+    const bool active = item < a.rows * a.hkv;
+    if (!active) item = a.rows * a.hkv - 1;               // valid addresses; result discarded
+    unsigned char *mine = lds + w * kTailWave;
+    attn_part_body<bf16_t, HD, G, kTailRows>(a, item / a.hkv, item % a.hkv, 0, threadIdx.x & 63, (float (*)[HD])mine,
+                                             mine + kTailQ, active);
+    return;
+  }
+  unsigned char *k_lds = lds, *vt_lds = lds + 32 * KSTR;
+  const int part = (int)blockIdx.x % a.bulk_parts, hk = ((int)blockIdx.x / a.bulk_parts) % a.hkv;
+  const int qgroup = (int)blockIdx.x / (a.bulk_parts * a.hkv);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, c = lane & 31, g = lane >> 5;
   // With a device-resident base (graph replay) the grid is sized for the longest context and the
   // blocks that exist are derived here; otherwise the host has computed them.
@@ -253,7 +277,7 @@ __global__ __launch_bounds__(NW * 64) void attn_bulk_kernel(AttnArgs a) {
   const int b_hi = min(b_lo + kBulkBlocksPerPart, n_blocks);
   if (b_lo >= b_hi) return;
 
-  const int r = (blockIdx.z * NW + wave) * 32 + c;
+  const int r = (qgroup * NW + wave) * 32 + c;
   const bool valid_q = r < a.rows * G;
   const int i = valid_q ? r / G : 0, gh = valid_q ? r % G : 0;
   const int n_incl = valid_q ? bulk_end(base + a.depth[i]) / 32 : 0;        // blocks [0, n_incl) belong to this row
@@ -370,8 +394,10 @@ __global__ __launch_bounds__(NW * 64) void attn_bulk_kernel(AttnArgs a) {
 }
 
 template <int HD, int G, int NW>
-static hipError_t launch_bulk(const AttnArgs &a, int n_bulk_parts, int q_groups, hipStream_t st) {
-  hipLaunchKernelGGL((attn_bulk_kernel<HD, G, NW>), dim3(n_bulk_parts, a.hkv, q_groups), dim3(NW * 64), 0, st, a);
+static hipError_t launch_hybrid(AttnArgs a, int q_groups, hipStream_t st) {
+  a.q_groups = q_groups;
+  const int n_tail = (a.rows * a.hkv + TailWaves<NW>::value - 1) / TailWaves<NW>::value;
+  hipLaunchKernelGGL((attn_hybrid_kernel<HD, G, NW>), dim3(a.bulk_parts * a.hkv * q_groups + n_tail), dim3(NW * 64), 0, st, a);
   return hipGetLastError();
 }
 
@@ -379,29 +405,24 @@ template <typename T, int HD, int G>
 static hipError_t launch_thg(AttnArgs a, int max_pos, hipStream_t st) {
   hipError_t e;
   if (sizeof(T) == 2) {
-    // hybrid: matrix-core bulk over [0, A(max_pos)) + vector tail per row
+    // hybrid: matrix-core bulk over [0, A(max_pos)) and the vector tail of every row in one launch
     a.tail_only = 1;
     a.bulk_blocks = bulk_end(max_pos) / 32;
-    const int n_bulk_parts = (a.bulk_blocks + kBulkBlocksPerPart - 1) / kBulkBlocksPerPart;
-    if (n_bulk_parts > a.max_parts) return hipErrorInvalidValue;
-    if (n_bulk_parts > 0) {
-      const int qblocks = (a.rows * G + 31) / 32;
-      if (qblocks <= 1) e = launch_bulk<HD, G, 1>(a, n_bulk_parts, 1, st);
-      else if (qblocks <= 2) e = launch_bulk<HD, G, 2>(a, n_bulk_parts, 1, st);
-      else if (qblocks <= 4) e = launch_bulk<HD, G, 4>(a, n_bulk_parts, 1, st);
-      else e = launch_bulk<HD, G, 8>(a, n_bulk_parts, (qblocks + 7) / 8, st);
-      if (e != hipSuccess) return e;
-    }
-    hipLaunchKernelGGL((attn_part_kernel<T, HD, G>), dim3(a.rows, a.hkv, 1), dim3(64), 0, st, a);
-    return hipGetLastError();
+    a.bulk_parts = (a.bulk_blocks + kBulkBlocksPerPart - 1) / kBulkBlocksPerPart;
+    if (a.bulk_parts + 1 > a.max_parts) return hipErrorInvalidValue;
+    const int qblocks = (a.rows * G + 31) / 32;
+    if (qblocks <= 1) e = launch_hybrid<HD, G, 1>(a, 1, st);
+    else if (qblocks <= 2) e = launch_hybrid<HD, G, 2>(a, 1, st);
+    else if (qblocks <= 4) e = launch_hybrid<HD, G, 4>(a, 1, st);
+    else e = launch_hybrid<HD, G, 8>(a, (qblocks + 7) / 8, st);
   } else {
     a.tail_only = 0;
     a.bulk_blocks = 0;
     const int n_parts = max_pos / kAttnPart + 1;
     if (n_parts > a.max_parts) return hipErrorInvalidValue;
     hipLaunchKernelGGL((attn_part_kernel<T, HD, G>), dim3(a.rows, a.hkv, n_parts), dim3(64), 0, st, a);
+    e = hipGetLastError();
   }
-  e = hipGetLastError();
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL((attn_combine_kernel<T, HD>), dim3(a.rows, a.hq), dim3(HD), 0, st, a);
   return hipGetLastError();

@@ -50,6 +50,31 @@ __device__ __forceinline__ int wave_sum_i(int x) {
   return x;
 }
 
+// Order-independent reductions (max, min) without LDS traffic: four DPP exchanges inside each row of 16
+// lanes (xor 1, xor 2, mirror within 8, mirror within 16), then the four row results are read lane by lane.
+// Needs all 64 lanes active.  Every lane gets the result.
+template <int CTRL> __device__ __forceinline__ int dpp_i32(int x) { return __builtin_amdgcn_update_dpp(0, x, CTRL, 0xF, 0xF, true); }
+template <int CTRL> __device__ __forceinline__ float dpp_f32(float x) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xF, 0xF, true));
+}
+__device__ __forceinline__ float wave_max_dpp(float x) {
+  x = fmaxf(x, dpp_f32<0xB1>(x));     // quad_perm [1,0,3,2]
+  x = fmaxf(x, dpp_f32<0x4E>(x));     // quad_perm [2,3,0,1]
+  x = fmaxf(x, dpp_f32<0x141>(x));    // row_half_mirror
+  x = fmaxf(x, dpp_f32<0x140>(x));    // row_mirror
+  const int b = __float_as_int(x);
+  return fmaxf(fmaxf(__int_as_float(__builtin_amdgcn_readlane(b, 0)), __int_as_float(__builtin_amdgcn_readlane(b, 16))),
+               fmaxf(__int_as_float(__builtin_amdgcn_readlane(b, 32)), __int_as_float(__builtin_amdgcn_readlane(b, 48))));
+}
+__device__ __forceinline__ int wave_min_dpp(int x) {
+  x = min(x, dpp_i32<0xB1>(x));
+  x = min(x, dpp_i32<0x4E>(x));
+  x = min(x, dpp_i32<0x141>(x));
+  x = min(x, dpp_i32<0x140>(x));
+  return min(min(__builtin_amdgcn_readlane(x, 0), __builtin_amdgcn_readlane(x, 16)),
+             min(__builtin_amdgcn_readlane(x, 32), __builtin_amdgcn_readlane(x, 48)));
+}
+
 // (value, index) pair ordered by larger value first, then lower index.
 struct ValIdx { float v; int i; };
 __device__ __forceinline__ bool better(float v, int i, float v2, int i2) { return v > v2 || (v == v2 && i < i2); }
@@ -61,6 +86,29 @@ __device__ __forceinline__ ValIdx wave_best(ValIdx a) {
     if (better(ov, oi, a.v, a.i)) { a.v = ov; a.i = oi; }
   }
   return a;
+}
+
+// The same order as one unsigned 64-bit key (larger key = earlier): the value mapped monotonically to
+// unsigned (-0 folded into +0), then the complemented index.  An empty entry (index INT_MAX) gets key 0,
+// below every real entry.
+__device__ __forceinline__ uint64_t order_key(float v, int i) {
+  if (i == 0x7FFFFFFF) return 0ull;
+  uint32_t u = __float_as_uint(v + 0.f);
+  u ^= (u >> 31) ? 0xFFFFFFFFu : 0x80000000u;
+  return ((uint64_t)u << 32) | (uint32_t)(0x7FFFFFFF - i);
+}
+// Number of keys ordered before key `k` held at list position `me`: larger keys, and equal keys (empty
+// entries) at earlier positions.  `keys` is in LDS, 16-byte aligned, n2 (even) entries, zero-padded.
+__device__ __forceinline__ int key_rank(const uint64_t *keys, int n2, uint64_t k, int me) {
+  typedef __attribute__((ext_vector_type(2))) uint64_t u64x2_t;
+  int rank = 0;
+#pragma unroll 4
+  for (int o = 0; o < n2; o += 2) {
+    const u64x2_t kk = *(const u64x2_t *)(keys + o);
+    rank += (kk.x > k || (kk.x == k && o < me)) ? 1 : 0;
+    rank += (kk.y > k || (kk.y == k && o + 1 < me)) ? 1 : 0;
+  }
+  return rank;
 }
 
 // Block-wide sum for blocks of up to 16 waves; `sh` needs 16 floats.  Fixed order.

@@ -27,7 +27,7 @@
 //
 // Each wave owns one 32-row block of W for the workgroup's K range and all
 // token blocks; the four waves of a workgroup share the X slab.  Weight loads
-// run two iterations ahead through a three-stage register ring; the X slab is
+// run kStages - 1 iterations ahead through a register ring; the X slab is
 // double-buffered in LDS and prefetched one slab ahead through registers.
 //
 // Determinism: the value of P[s][i][col] depends only on row i of X, row col of
@@ -52,7 +52,11 @@ typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;   // native vector
 #ifndef SPEC_GEMM_SLAB_ITERS
 #define SPEC_GEMM_SLAB_ITERS 2
 #endif
+#ifndef SPEC_GEMM_STAGES
+#define SPEC_GEMM_STAGES 3
+#endif
 constexpr int kGemmWaves = SPEC_GEMM_WAVES;         // waves per workgroup
+constexpr int kStages = SPEC_GEMM_STAGES;           // register ring: weight loads run kStages - 1 iterations ahead
 constexpr int kGemmThreads = kGemmWaves * kWave;
 constexpr int kLaneBytes = 128;                     // contiguous weight bytes per lane per iteration
 constexpr int kSlabIters = SPEC_GEMM_SLAB_ITERS;    // iterations per LDS slab
@@ -74,8 +78,17 @@ __device__ __forceinline__ void mfma_step(f32x16_t &acc, const u32x4_t &x, const
   acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(x.w), __uint_as_float(w.w), acc, 0, 0, 0);
 }
 
+constexpr int gcd_ce(int a, int b) { return b == 0 ? a : gcd_ce(b, a % b); }
+template <int N, int I = 0, typename F>
+__device__ __forceinline__ void static_for(F &&f) {
+  if constexpr (I < N) {
+    f(std::integral_constant<int, I>{});
+    static_for<N, I + 1>(f);
+  }
+}
+
 template <typename T, int TB>
-__global__ __launch_bounds__(kGemmThreads, TB <= 2 ? 2 : 1) void gemm_stream_kernel(GemmArgs a) {
+__global__ __launch_bounds__(kGemmThreads, (TB <= 2 && kStages <= 3) ? 2 : 1) void gemm_stream_kernel(GemmArgs a) {
   constexpr int EPL = GemmTraits<T>::kEpl;
   constexpr int KI = 2 * kLaneBytes / (int)sizeof(T);         // k elements per iteration
   constexpr int XCH = TB * 32 * (kSlabRowBytes / 16) / kGemmThreads;   // 16-byte X chunks per thread per slab
@@ -122,7 +135,7 @@ __global__ __launch_bounds__(kGemmThreads, TB <= 2 ? 2 : 1) void gemm_stream_ker
 #pragma unroll
     for (int v = 0; v < 16; v++) acc[t][v] = 0.f;
 
-  u32x4_t ring[3][8];
+  u32x4_t ring[kStages][8];
   u32x4_t xr[XCH];
 
   // Every tile is complete in the packed layout (zero-padded), so weight loads need no guard and
@@ -166,14 +179,15 @@ __global__ __launch_bounds__(kGemmThreads, TB <= 2 ? 2 : 1) void gemm_stream_ker
   };
 
   load_x(0);
-  if (0 < n_iter) load_w(ring[0], 0);
-  if (1 < n_iter) load_w(ring[1], 1);
+#pragma unroll
+  for (int it = 0; it < kStages - 1; it++)
+    if (it < n_iter) load_w(ring[it], it);
   store_x(0);
   __syncthreads();
 
-  // The ring stage of iteration `it` is it % 3.  A slab is kSlabIters iterations, so three slabs
+  // The ring stage of iteration `it` is it % kStages.  A slab is kSlabIters iterations, so kPeriod slabs
   // form one period of the stage pattern and are unrolled with compile-time stage indices
-  // (P = slab index mod 3).  Steady state (FAST): every load of the slab is a full, in-range
+  // (P = slab index mod kPeriod).  Steady state (FAST): every load of the slab is a full, in-range
   // iteration and a next slab exists, so the body has no branch and the compiler keeps exact
   // outstanding-load counts; the remaining slabs take the guarded form.
   auto slab = [&](auto p_tag, auto fast_tag, int S) {
@@ -185,11 +199,11 @@ __global__ __launch_bounds__(kGemmThreads, TB <= 2 ? 2 : 1) void gemm_stream_ker
     if (more) load_x(S + 1);
 #pragma unroll
     for (int ii = 0; ii < kSlabIters; ii++) {
-      constexpr int base_stage = (kSlabIters * P) % 3;
+      constexpr int base_stage = (kSlabIters * P) % kStages;
       const int it = S * kSlabIters + ii;
-      // stage indices are compile-time after unrolling: (base_stage + ii) % 3 etc.
-      const int st_use = (base_stage + ii) % 3, st_load = (base_stage + ii + 2) % 3;
-      if (FAST || it + 2 < n_iter) load_w(ring[st_load], it + 2);
+      // stage indices are compile-time after unrolling
+      const int st_use = (base_stage + ii) % kStages, st_load = (base_stage + ii + kStages - 1) % kStages;
+      if (FAST || it + kStages - 1 < n_iter) load_w(ring[st_load], it + kStages - 1);
       __builtin_amdgcn_sched_barrier(0);                     // keep the prefetch ahead of the MFMAs
       if (FAST || it < n_iter) compute(ring[st_use], buf, ii);
       __builtin_amdgcn_sched_barrier(0);
@@ -197,20 +211,15 @@ __global__ __launch_bounds__(kGemmThreads, TB <= 2 ? 2 : 1) void gemm_stream_ker
     if (more) store_x(buf ^ 1);
     __syncthreads();
   };
-  using I0 = std::integral_constant<int, 0>; using I1 = std::integral_constant<int, 1>; using I2 = std::integral_constant<int, 2>;
-  // slabs S for which iteration S*kSlabIters + kSlabIters + 1 (the last one loaded) is in range
-  const int n_steady = n_iter >= kSlabIters + 2 ? (n_iter - 2) / kSlabIters : 0;
+  constexpr int kPeriod = kStages / gcd_ce(kStages, kSlabIters);
+  auto period = [&](auto fast_tag, int S0) {
+    static_for<kPeriod>([&](auto p_tag) { slab(p_tag, fast_tag, S0 + decltype(p_tag)::value); });
+  };
+  // slabs S whose last prefetch, iteration S*kSlabIters + kSlabIters - 1 + kStages - 1, is in range
+  const int n_steady = n_iter >= kSlabIters + kStages - 1 ? (n_iter - kStages + 1) / kSlabIters : 0;
   int s = 0;
-  for (; s + 3 <= n_steady; s += 3) {
-    slab(I0{}, std::true_type{}, s);
-    slab(I1{}, std::true_type{}, s + 1);
-    slab(I2{}, std::true_type{}, s + 2);
-  }
-  for (; s < n_slab; s += 3) {
-    slab(I0{}, std::false_type{}, s);
-    slab(I1{}, std::false_type{}, s + 1);
-    slab(I2{}, std::false_type{}, s + 2);
-  }
+  for (; s + kPeriod <= n_steady; s += kPeriod) period(std::true_type{}, s);
+  for (; s < n_slab; s += kPeriod) period(std::false_type{}, s);
 
   if (swiglu) {
     // the up waves hand their tiles to the gate waves through LDS (the X slabs are no longer needed)

@@ -78,13 +78,17 @@ struct AttnArgs {
   float *part;                          // scratch: [rows][hq][max_parts][hd + 2]; max_parts >= max_pos/kAttnPart + 2
   int max_parts;
   void *out;
-  int tail_only, bulk_blocks;           // set by launch_attention (hybrid matrix-core / vector split)
+  int tail_only, bulk_blocks, bulk_parts, q_groups;   // set by launch_attention (hybrid matrix-core / vector split)
 };
 hipError_t launch_attention(int dtype, const AttnArgs &a, int max_pos, hipStream_t st);
 
 // ---- select.hip ------------------------------------------------------------------------------
-// argmax over each row of logits [rows, vocab] (ld = vocab), lower index on ties.
-hipError_t launch_rows_argmax(const float *logits, int rows, int vocab, int *out, hipStream_t st);
+// argmax over each row of logits [rows, vocab] (ld = vocab), lower index on ties.  Per-slice results go to
+// part_val / part_idx [rows][argmax_slices(vocab)]; if `out` is not null a second kernel merges them into
+// out[row] (the greedy acceptance merges the slices itself).
+int argmax_slices(int vocab);
+hipError_t launch_rows_argmax(const float *logits, int rows, int vocab, float *part_val, int *part_idx, int *out,
+                              hipStream_t st);
 // per row, with x = logit / temp: stats[row] = {max x, sum exp(x - max x)}
 hipError_t launch_rows_softmax_stats(const float *logits, int rows, int vocab, float temp, float2 *stats, hipStream_t st);
 // per row: top-k (token, log-softmax) pairs, best first, lower token on ties.  Two stages through scratch.
@@ -121,8 +125,8 @@ struct AcceptResult {                   // lives on the device; copied to the ho
   int node[kMaxDepth + 1];              // node[0] = 0 (root), node[d] = accepted node of depth d
   int token[kMaxDepth + 1];             // m accepted tokens then the bonus token
 };
-hipError_t launch_accept_greedy(const int *row_argmax, const int *tree_tok, const int *tree_par, int n_nodes,
-                                AcceptResult *res, hipStream_t st);
+hipError_t launch_accept_greedy(const float *amax_val, const int *amax_idx, int n_slices, const int *tree_tok,
+                                const int *tree_par, int n_nodes, AcceptResult *res, hipStream_t st);
 hipError_t launch_accept_sample(const float *logits, int vocab, const float2 *stats, float temp, const int *tree_tok,
                                 const int *tree_par, int n_nodes, uint64_t seed, uint32_t cycle, AcceptResult *res,
                                 hipStream_t st);

@@ -118,14 +118,30 @@ hipError_t launch_embed_norm(int dtype, const void *embed, const int *token, int
   return hipGetLastError();
 }
 
+// One workgroup per row; 16-byte pieces, all loads of a thread issued before its stores.
 template <typename T>
 __global__ __launch_bounds__(kRowThreads) void concat_feat_embed_kernel(const T *feat, const int *src_row, const T *embed,
                                                                         const int *token, int d, T *xcat) {
+  typedef __attribute__((ext_vector_type(4))) uint32_t piece_t;
+  constexpr int MAXP = 4;                                   // pieces per thread and half handled per pass
   const int i = blockIdx.x;
-  const T *f = feat + (size_t)(src_row ? src_row[i] : i) * d;
-  const T *e = embed + (size_t)token[i] * d;
-  T *o = xcat + (size_t)i * 2 * d;
-  for (int c = threadIdx.x; c < d; c += kRowThreads) { o[c] = f[c]; o[d + c] = e[c]; }
+  const piece_t *f = (const piece_t *)(feat + (size_t)(src_row ? src_row[i] : i) * d);
+  const piece_t *e = (const piece_t *)(embed + (size_t)token[i] * d);
+  piece_t *o = (piece_t *)(xcat + (size_t)i * 2 * d);
+  const int np = d * (int)sizeof(T) / 16;                   // pieces per half (d * sizeof(T) is a multiple of 16)
+  for (int c0 = 0; c0 < np; c0 += MAXP * kRowThreads) {
+    piece_t a[MAXP], b[MAXP];
+#pragma unroll
+    for (int u = 0; u < MAXP; u++) {
+      const int c = min(c0 + u * kRowThreads + (int)threadIdx.x, np - 1);
+      a[u] = f[c]; b[u] = e[c];
+    }
+#pragma unroll
+    for (int u = 0; u < MAXP; u++) {
+      const int c = c0 + u * kRowThreads + (int)threadIdx.x;
+      if (c < np) { o[c] = a[u]; o[np + c] = b[u]; }
+    }
+  }
 }
 
 hipError_t launch_concat_feat_embed(int dtype, const void *feat, const int *src_row, const void *embed,

@@ -35,21 +35,56 @@ __device__ __forceinline__ float rng_gumbel(uint64_t stream, int v) {
 }
 
 // ---- per-row argmax ------------------------------------------------------------------------
-__global__ __launch_bounds__(kSelThreads) void rows_argmax_kernel(const float *logits, int vocab, int *out) {
+// Stage 1: one workgroup per (slice of kTopkSlice entries, row) leaves the slice's best (value, index)
+// in part_val / part_idx [rows][n_slices].  The consumer (greedy acceptance, or the finishing kernel)
+// merges a row's slices with the same ordering rule, so the result is the row's first maximum.
+__global__ __launch_bounds__(kSelThreads) void argmax_slice_kernel(const float *logits, int vocab, int n_slices,
+                                                                   float *part_val, int *part_idx) {
+  constexpr int PER = kTopkSlice / kSelThreads;   // 16
   __shared__ float shv[16];
   __shared__ int shi[16];
-  const float *row = logits + (size_t)blockIdx.x * vocab;
+  const int slice = blockIdx.x, rowi = blockIdx.y, t = threadIdx.x;
+  const int c0 = slice * kTopkSlice;
+  const float *row = logits + (size_t)rowi * vocab;
+  float v[PER];
+#pragma unroll
+  for (int e = 0; e < PER; e++) {
+    const int c = c0 + t + e * kSelThreads;
+    v[e] = c < vocab ? row[c] : -INFINITY;
+  }
   ValIdx b{-INFINITY, INT_MAX};
-  for (int c = threadIdx.x; c < vocab; c += kSelThreads) {
-    const float x = row[c];
-    if (x > b.v || b.i == INT_MAX) { b.v = x; b.i = c; }     // ascending c: strict > keeps the lower index
+#pragma unroll
+  for (int e = 0; e < PER; e++) {
+    const int c = c0 + t + e * kSelThreads;
+    if (c < vocab && (v[e] > b.v || b.i == INT_MAX)) { b.v = v[e]; b.i = c; }   // ascending c: strict > keeps the lower index
   }
   b = block_best(b, shv, shi);
-  if (threadIdx.x == 0) out[blockIdx.x] = b.i;
+  if (t == 0) { part_val[(size_t)rowi * n_slices + slice] = b.v; part_idx[(size_t)rowi * n_slices + slice] = b.i; }
 }
-hipError_t launch_rows_argmax(const float *logits, int rows, int vocab, int *out, hipStream_t st) {
+// One wavefront: best of a row's slice results.
+__device__ __forceinline__ int merge_argmax(const float *part_val, const int *part_idx, int n_slices, int row, int lane) {
+  ValIdx b{-INFINITY, INT_MAX};
+  for (int sl = lane; sl < n_slices; sl += 64) {
+    const float x = part_val[(size_t)row * n_slices + sl];
+    const int c = part_idx[(size_t)row * n_slices + sl];
+    if (better(x, c, b.v, b.i)) { b.v = x; b.i = c; }
+  }
+  return wave_best(b).i;
+}
+__global__ __launch_bounds__(64) void argmax_finish_kernel(const float *part_val, const int *part_idx, int n_slices, int *out) {
+  const int best = merge_argmax(part_val, part_idx, n_slices, blockIdx.x, threadIdx.x);
+  if (threadIdx.x == 0) out[blockIdx.x] = best;
+}
+int argmax_slices(int vocab) { return (vocab + kTopkSlice - 1) / kTopkSlice; }
+hipError_t launch_rows_argmax(const float *logits, int rows, int vocab, float *part_val, int *part_idx, int *out,
+                              hipStream_t st) {
   if (rows < 1 || vocab < 1) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(rows_argmax_kernel, dim3(rows), dim3(kSelThreads), 0, st, logits, vocab, out);
+  const int n_slices = argmax_slices(vocab);
+  hipLaunchKernelGGL(argmax_slice_kernel, dim3(n_slices, rows), dim3(kSelThreads), 0, st, logits, vocab, n_slices, part_val,
+                     part_idx);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess || out == nullptr) return e;
+  hipLaunchKernelGGL(argmax_finish_kernel, dim3(rows), dim3(64), 0, st, part_val, part_idx, n_slices, out);
   return hipGetLastError();
 }
 
@@ -74,13 +109,16 @@ hipError_t launch_rows_softmax_stats(const float *logits, int rows, int vocab, f
 
 // ---- per-row top-k log-probabilities -------------------------------------------------------
 // Stage 1: one workgroup per (slice of kTopkSlice entries, row): slice max, slice sum-exp and the
-// slice's k best entries, found by k rounds of block-wide argmax over register-resident values.
+// slice's k best entries.  Each wavefront finds the k best of its own 1024 register-resident values by k
+// rounds of a wave-wide argmax (shuffles only); the 4k finalists are then placed by rank.
 __global__ __launch_bounds__(kSelThreads) void topk_slice_kernel(const float *logits, int vocab, int k, int n_slices,
                                                                  float *sc_val, int *sc_idx, float2 *sc_stat) {
   constexpr int PER = kTopkSlice / kSelThreads;   // 16
+  constexpr int NWV = kSelThreads / 64;
   __shared__ float shv[16];
-  __shared__ int shi[16];
-  const int slice = blockIdx.x, rowi = blockIdx.y, t = threadIdx.x;
+  __shared__ float cv[NWV * kMaxTopK];
+  __shared__ __attribute__((aligned(16))) uint64_t keys[NWV * kMaxTopK + 2];
+  const int slice = blockIdx.x, rowi = blockIdx.y, t = threadIdx.x, lane = t & 63, wave = t >> 6;
   const int c0 = slice * kTopkSlice;
   const float *row = logits + (size_t)rowi * vocab;
   float v[PER];
@@ -101,64 +139,82 @@ __global__ __launch_bounds__(kSelThreads) void topk_slice_kernel(const float *lo
   if (t == 0) sc_stat[o] = make_float2(m, s);
   uint32_t taken = 0;
   for (int r = 0; r < k; r++) {
-    ValIdx b{-INFINITY, INT_MAX};
+    // best remaining value of the wave, then the lowest index carrying it
+    float mv = -INFINITY;
 #pragma unroll
-    for (int e = 0; e < PER; e++) {
+    for (int e = 0; e < PER; e++) mv = fmaxf(mv, ((taken >> e) & 1u) ? -INFINITY : v[e]);
+    const float best_v = wave_max_dpp(mv);
+    int mi = INT_MAX;
+#pragma unroll
+    for (int e = PER - 1; e >= 0; e--) {
       const int c = c0 + t + e * kSelThreads;
-      if (!((taken >> e) & 1u) && c < vocab && (v[e] > b.v || b.i == INT_MAX)) { b.v = v[e]; b.i = c; }
+      if (!((taken >> e) & 1u) && c < vocab && v[e] == best_v) mi = c;
     }
-    b = block_best(b, shv, shi);
-    if (t == 0) { sc_val[o * kMaxTopK + r] = b.v; sc_idx[o * kMaxTopK + r] = b.i; }
-    if (b.i != INT_MAX && (b.i - c0) % kSelThreads == t) taken |= 1u << ((b.i - c0) / kSelThreads);
+    const int best_i = wave_min_dpp(mi);
+    if (lane == 0) { keys[wave * k + r] = order_key(best_v, best_i); cv[wave * k + r] = best_v; }
+    if (best_i != INT_MAX && (best_i - c0) % kSelThreads == t) taken |= 1u << ((best_i - c0) / kSelThreads);
+  }
+  if (t < 2) keys[NWV * k + t] = 0ull;                       // padding for the pairwise reads
+  __syncthreads();
+  if (t < NWV * k) {
+    const uint64_t key = keys[t];
+    const int rank = key_rank(keys, (NWV * k + 1) & ~1, key, t);
+    if (rank < k) {
+      const bool valid = key != 0ull;
+      sc_val[o * kMaxTopK + rank] = valid ? cv[t] : -INFINITY;
+      sc_idx[o * kMaxTopK + rank] = valid ? 0x7FFFFFFF - (int)(uint32_t)key : INT_MAX;
+    }
   }
 }
-// Stage 2: one wavefront per row merges the slices: log-sum-exp and the k best of all candidates.
-__global__ __launch_bounds__(64) void topk_merge_kernel(int k, int n_slices, const float *sc_val, const int *sc_idx,
-                                                        const float2 *sc_stat, int *top_tok, float *top_lp) {
-  const int rowi = blockIdx.x, lane = threadIdx.x;
-  const float2 *stat = sc_stat + (size_t)rowi * n_slices;
-  float m = -INFINITY;
-  for (int s = lane; s < n_slices; s += 64) m = fmaxf(m, stat[s].x);
-  m = wave_max(m);
-  float tot = 0.f;
-  for (int s0 = 0; s0 < n_slices; s0 += 64) {            // slices in ascending groups of 64, fixed butterfly inside
-    const int s = s0 + lane;
-    tot += wave_sum(s < n_slices ? stat[s].y * expf(stat[s].x - m) : 0.f);
-  }
-  const float lse = m + logf(tot);
+// Stage 2: one workgroup per row merges the slices: log-sum-exp (first wavefront) and the k best of all
+// slice candidates, placed by rank.
+constexpr int kMaxMergeCand = 4096;
+__global__ __launch_bounds__(kSelThreads) void topk_merge_kernel(int k, int n_slices, const float *sc_val, const int *sc_idx,
+                                                                 const float2 *sc_stat, int *top_tok, float *top_lp) {
+  __shared__ __attribute__((aligned(16))) uint64_t keys[kMaxMergeCand + 2];
+  __shared__ float lse_sh;
+  const int rowi = blockIdx.x, t = threadIdx.x;
   const int n_cand = n_slices * k;                          // candidate id = slice * k + r
+  const int n2 = (n_cand + 1) & ~1;
   const float *val = sc_val + (size_t)rowi * n_slices * kMaxTopK;
   const int *idx = sc_idx + (size_t)rowi * n_slices * kMaxTopK;
-  // a lane's candidates: ids lane, lane + 64, ...; taken ones are marked in a bitmask (<= 64 per lane)
-  uint64_t taken = 0;
-  for (int r = 0; r < k; r++) {
-    ValIdx b{-INFINITY, INT_MAX};
-    int e = 0;
-    for (int id = lane; id < n_cand; id += 64, e++) {
-      if ((taken >> e) & 1ull) continue;
-      const int sl = id / k, rr = id % k;
-      const float x = val[sl * kMaxTopK + rr];
-      const int c = idx[sl * kMaxTopK + rr];
-      if (c != INT_MAX && better(x, c, b.v, b.i)) { b.v = x; b.i = c; }
+  for (int id = t; id < n2; id += kSelThreads) {
+    const int sl = id / k, rr = id % k;
+    keys[id] = id < n_cand ? order_key(val[sl * kMaxTopK + rr], idx[sl * kMaxTopK + rr]) : 0ull;
+  }
+  if (t < 64) {
+    const float2 *stat = sc_stat + (size_t)rowi * n_slices;
+    float m = -INFINITY;
+    for (int sl = t; sl < n_slices; sl += 64) m = fmaxf(m, stat[sl].x);
+    m = wave_max(m);
+    float tot = 0.f;
+    for (int s0 = 0; s0 < n_slices; s0 += 64) {            // slices in ascending groups of 64, fixed butterfly inside
+      const int sl = s0 + t;
+      tot += wave_sum(sl < n_slices ? stat[sl].y * expf(stat[sl].x - m) : 0.f);
     }
-    b = wave_best(b);
-    e = 0;
-    for (int id = lane; id < n_cand; id += 64, e++) {
+    if (t == 0) lse_sh = m + logf(tot);
+  }
+  __syncthreads();
+  const float lse = lse_sh;
+  for (int id = t; id < n_cand; id += kSelThreads) {
+    const uint64_t key = keys[id];
+    const int rank = key_rank(keys, n2, key, id);
+    if (rank < k) {
       const int sl = id / k, rr = id % k;
-      if (idx[sl * kMaxTopK + rr] == b.i && b.i != INT_MAX) taken |= 1ull << e;
+      top_tok[rowi * kMaxTopK + rank] = idx[sl * kMaxTopK + rr];
+      top_lp[rowi * kMaxTopK + rank] = val[sl * kMaxTopK + rr] - lse;
     }
-    if (lane == 0) { top_tok[rowi * kMaxTopK + r] = b.i; top_lp[rowi * kMaxTopK + r] = b.v - lse; }
   }
 }
 hipError_t launch_rows_topk_logprob(const float *logits, int rows, int vocab, int k, float *sc_val, int *sc_idx,
                                     float2 *sc_stat, int *top_tok, float *top_lp, hipStream_t st) {
   const int n_slices = (vocab + kTopkSlice - 1) / kTopkSlice;
-  if (rows < 1 || k < 1 || k > kMaxTopK || k > vocab || n_slices * k > 64 * 64) return hipErrorInvalidValue;
+  if (rows < 1 || k < 1 || k > kMaxTopK || k > vocab || n_slices * k > kMaxMergeCand) return hipErrorInvalidValue;
   hipLaunchKernelGGL(topk_slice_kernel, dim3(n_slices, rows), dim3(kSelThreads), 0, st, logits, vocab, k, n_slices, sc_val,
                      sc_idx, sc_stat);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(topk_merge_kernel, dim3(rows), dim3(64), 0, st, k, n_slices, sc_val, sc_idx, sc_stat, top_tok, top_lp);
+  hipLaunchKernelGGL(topk_merge_kernel, dim3(rows), dim3(kSelThreads), 0, st, k, n_slices, sc_val, sc_idx, sc_stat, top_tok, top_lp);
   return hipGetLastError();
 }
 
@@ -226,48 +282,58 @@ hipError_t launch_pool_expand(const DraftState &s, const int *top_tok, const flo
 
 // ---- rerank --------------------------------------------------------------------------------
 constexpr int kMaxPool = kMaxTopK + (kMaxDepth - 1) * kMaxTopK * kMaxTopK;    // 3600
-__global__ __launch_bounds__(kSelThreads) void rerank_kernel(DraftState s, int total, const int *root_tok, int *tree_n,
-                                                             int *tree_tok, int *tree_par, int *tree_dep, float *tree_sc) {
-  __shared__ float sc[kMaxPool];
-  __shared__ short node_of[kMaxPool];                       // 0 = not kept, else node index
+constexpr int kPoolWords = (kMaxPool + 31) / 32;
+constexpr int kRerankThreads = 1024;
+__global__ __launch_bounds__(kRerankThreads) void rerank_kernel(DraftState s, int total, const int *root_tok, int *tree_n,
+                                                                int *tree_tok, int *tree_par, int *tree_dep, float *tree_sc) {
+  typedef __attribute__((ext_vector_type(4))) float f32x4_t;
+  __shared__ __attribute__((aligned(16))) float sc[kMaxPool + 4];
+  __shared__ uint32_t kept[kPoolWords];                     // bit c: pool entry c is in the tree
+  __shared__ int before[kPoolWords];                        // kept entries in earlier words
   const int t = threadIdx.x, n = *s.n_pool;
   const int keep = min(total - 1, n);
-  for (int c = t; c < n; c += kSelThreads) sc[c] = s.pool_sc[c];
+  const int n_words = (n + 31) / 32, n4 = (n + 3) & ~3;
+  for (int c = t; c < n4; c += kRerankThreads) sc[c] = c < n ? s.pool_sc[c] + 0.f : -INFINITY;
+  for (int w = t; w < n_words; w += kRerankThreads) kept[w] = 0u;
   __syncthreads();
-  for (int c = t; c < n; c += kSelThreads) {
-    int rank = 0;
+  for (int c = t; c < n; c += kRerankThreads) {
+    // rank = entries with a larger score, plus equal scores at a lower pool index
     const float v = sc[c];
-    for (int o = 0; o < n; o++) rank += better(sc[o], o, v, c) ? 1 : 0;
-    node_of[c] = rank < keep ? 1 : 0;
+    int rank = 0;
+#pragma unroll 2
+    for (int o = 0; o < n4; o += 4) {
+      const f32x4_t x = *(const f32x4_t *)(sc + o);
+      rank += (x.x > v || (x.x == v && o < c)) ? 1 : 0;
+      rank += (x.y > v || (x.y == v && o + 1 < c)) ? 1 : 0;
+      rank += (x.z > v || (x.z == v && o + 2 < c)) ? 1 : 0;
+      rank += (x.w > v || (x.w == v && o + 3 < c)) ? 1 : 0;
+    }
+    if (rank < keep) atomicOr(&kept[c >> 5], 1u << (c & 31));
+  }
+  __syncthreads();
+  for (int w = t; w < n_words; w += kRerankThreads) {
+    int cnt = 0;
+    for (int u = 0; u < w; u++) cnt += __popc(kept[u]);
+    before[w] = cnt;
   }
   __syncthreads();
   // node index = 1 + number of kept entries with a lower pool index (kept in pool order: parents first)
-  int my_nodes[(kMaxPool + kSelThreads - 1) / kSelThreads];
-  int e = 0;
-  for (int c = t; c < n; c += kSelThreads, e++) {
-    int cnt = 0;
-    if (node_of[c]) for (int o = 0; o < c; o++) cnt += node_of[o] ? 1 : 0;
-    my_nodes[e] = node_of[c] ? cnt + 1 : 0;
-  }
-  __syncthreads();
-  e = 0;
-  for (int c = t; c < n; c += kSelThreads, e++) node_of[c] = (short)my_nodes[e];
-  __syncthreads();
-  for (int c = t; c < n; c += kSelThreads) {
-    const int j = node_of[c];
-    if (!j) continue;
+  auto node_of = [&](int c) { return 1 + before[c >> 5] + __popc(kept[c >> 5] & ((1u << (c & 31)) - 1u)); };
+  for (int c = t; c < n; c += kRerankThreads) {
+    if (!((kept[c >> 5] >> (c & 31)) & 1u)) continue;
+    const int j = node_of(c);
     const int par = s.pool_par[c];
     tree_tok[j] = s.pool_tok[c];
-    tree_par[j] = par < 0 ? 0 : node_of[par];
+    tree_par[j] = par < 0 ? 0 : node_of(par);               // a parent outscores (or ties at a lower index) its children, so it is kept
     tree_dep[j] = s.pool_dep[c];
-    tree_sc[j] = sc[c];
+    tree_sc[j] = s.pool_sc[c];
   }
   if (t == 0) { tree_tok[0] = *root_tok; tree_par[0] = -1; tree_dep[0] = 0; tree_sc[0] = 0.f; *tree_n = keep + 1; }
 }
 hipError_t launch_rerank(const DraftState &s, int total, const int *root_tok, int *tree_n, int *tree_tok, int *tree_par,
                          int *tree_dep, float *tree_sc, hipStream_t st) {
   if (total < 1 || total > kMaxNodes) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(rerank_kernel, dim3(1), dim3(kSelThreads), 0, st, s, total, root_tok, tree_n, tree_tok, tree_par, tree_dep,
+  hipLaunchKernelGGL(rerank_kernel, dim3(1), dim3(kRerankThreads), 0, st, s, total, root_tok, tree_n, tree_tok, tree_par, tree_dep,
                      tree_sc);
   return hipGetLastError();
 }
@@ -281,13 +347,14 @@ __device__ __forceinline__ int find_child(const int *tree_tok, const int *tree_p
   return wave_min_i(best);
 }
 
-__global__ __launch_bounds__(64) void accept_greedy_kernel(const int *row_argmax, const int *tree_tok, const int *tree_par,
-                                                           int n_nodes, AcceptResult *res) {
+__global__ __launch_bounds__(64) void accept_greedy_kernel(const float *amax_val, const int *amax_idx, int n_slices,
+                                                           const int *tree_tok, const int *tree_par, int n_nodes,
+                                                           AcceptResult *res) {
   const int lane = threadIdx.x;
   int cur = 0, m = 0;
   if (lane == 0) res->node[0] = 0;
   for (int step = 0; step <= kMaxDepth; step++) {
-    const int best = row_argmax[cur];
+    const int best = merge_argmax(amax_val, amax_idx, n_slices, cur, lane);   // argmax of the target's row
     const int c = m < kMaxDepth ? find_child(tree_tok, tree_par, n_nodes, cur, best, lane) : INT_MAX;
     if (lane == 0) res->token[m] = best;                    // accepted token, or the bonus when the walk stops
     if (c == INT_MAX) break;
@@ -296,10 +363,11 @@ __global__ __launch_bounds__(64) void accept_greedy_kernel(const int *row_argmax
   }
   if (lane == 0) res->n_acc = m;
 }
-hipError_t launch_accept_greedy(const int *row_argmax, const int *tree_tok, const int *tree_par, int n_nodes,
-                                AcceptResult *res, hipStream_t st) {
-  if (n_nodes < 1 || n_nodes > kMaxNodes) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(accept_greedy_kernel, dim3(1), dim3(64), 0, st, row_argmax, tree_tok, tree_par, n_nodes, res);
+hipError_t launch_accept_greedy(const float *amax_val, const int *amax_idx, int n_slices, const int *tree_tok,
+                                const int *tree_par, int n_nodes, AcceptResult *res, hipStream_t st) {
+  if (n_nodes < 1 || n_nodes > kMaxNodes || n_slices < 1) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(accept_greedy_kernel, dim3(1), dim3(64), 0, st, amax_val, amax_idx, n_slices, tree_tok, tree_par, n_nodes,
+                     res);
   return hipGetLastError();
 }
 
