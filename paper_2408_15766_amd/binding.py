@@ -304,7 +304,7 @@ class Engine:
     """Owns the torch-allocated workspace and the weight pointer table of one libspec context."""
 
     def __init__(self, shape, weights: Dict[str, "object"], *, max_seq: Optional[int] = None, temperature: Optional[float] = None,
-                 seed: int = 0, tree=None, device: int = 0, graphs: bool = True):
+                 seed: int = 0, tree=None, device: int = 0, graphs: bool = True, workspace_fill: int = 0):
         import torch
         self.shape = shape
         # a stream of its own (default priority): graph capture is not possible on the default stream
@@ -322,7 +322,8 @@ class Engine:
         nbytes = spec_workspace_bytes(cfg)
         if nbytes == 0:
             raise SpecError(SPEC_EINVAL, "invalid configuration")
-        self.workspace = torch.zeros(nbytes, dtype=torch.uint8, device=f"cuda:{device}")
+        # the library initialises what it reads; `workspace_fill` lets a test hand over a dirty workspace
+        self.workspace = torch.full((nbytes,), workspace_fill, dtype=torch.uint8, device=f"cuda:{device}")
         cfg.workspace = self.workspace.data_ptr()
         cfg.workspace_bytes = nbytes
         self.cfg = cfg
@@ -339,7 +340,7 @@ class Engine:
         for f in LAYER_FIELDS:
             setattr(w.draft_layer, f, weights[f"draft.{f}"].data_ptr())
         self._w = w
-        torch.cuda.synchronize(device)                  # workspace zero-fill done before the library's stream uses it
+        torch.cuda.synchronize(device)                  # workspace fill done before the library's stream uses it
         self.ctx = spec_create(cfg, w)
         if not graphs:
             spec_set_graphs(self.ctx, False)

@@ -56,8 +56,8 @@ template <> struct Chunk<bf16_t> {
   }
 };
 
-// End of the bulk region of a row at position p (a multiple of 32, <= p - kMaxDepth): see the header.
-__device__ __host__ __forceinline__ int bulk_end(int p) { return p > kMaxDepth ? ((p - kMaxDepth) / 32) * 32 : 0; }
+// End of the bulk region of a row at position p: the tail is the last kMaxDepth + 1 positions.  See the header.
+__device__ __host__ __forceinline__ int bulk_end(int p) { return p > kMaxDepth ? p - kMaxDepth : 0; }
 
 // Orders this wavefront's LDS writes before its later LDS reads of other lanes' data.  The LDS executes
 // one wavefront's operations in issue order, so only the compiler has to be kept from reordering them.
@@ -73,10 +73,7 @@ __device__ __forceinline__ void wave_lds_sync() {
 template <typename T> struct PartLds {
   static constexpr int vrow(int hd) { return hd * (int)sizeof(T) + 16; }   // +16: conflict-free row writes
 };
-// VR = staged value rows the caller provides: 64 in general; the tail range never exceeds 32 + kMaxDepth keys.
-constexpr int kTailRows = 48;
-static_assert(32 + kMaxDepth <= kTailRows && kTailRows % 8 == 0, "tail staging area too small");
-template <typename T, int HD, int G, int VR>
+template <typename T, int HD, int G>
 __device__ __forceinline__ void attn_part_body(const AttnArgs &a, int i, int hk, int part, int lane, float (*qs)[HD],
                                                unsigned char *vs, bool store) {
   constexpr int EPL = Chunk<T>::kEpl;
@@ -84,9 +81,8 @@ __device__ __forceinline__ void attn_part_body(const AttnArgs &a, int i, int hk,
   constexpr int VROW = PartLds<T>::vrow(HD);         // LDS bytes per staged value row
   const int base = a.base_ptr ? *a.base_ptr : a.base;  // device-resident when the launch is replayed from a graph
   const int p = base + a.depth[i];
-  // full mode: part `part` of the whole range [0, p]; tail mode: the single range [A(p), p]
-  const int k_lo = a.tail_only ? bulk_end(p) : part * kAttnPart;
-  const int k_hi = a.tail_only ? p + 1 : min(p + 1, k_lo + kAttnPart);
+  const int k_lo = part * kAttnPart;
+  const int k_hi = min(p + 1, k_lo + kAttnPart);
   if (k_lo >= k_hi) return;
 
   const float *qrow = (const float *)a.q + ((size_t)i * a.hq + (size_t)hk * G) * HD;   // queries are fp32
@@ -108,8 +104,9 @@ __device__ __forceinline__ void attn_part_body(const AttnArgs &a, int i, int hk,
     // lane = key: this lane's key row and value row (all loads issued before anything is used)
     const int kq = kb + lane;
     const bool valid = kq < k_hi;
-    int slot = 0;
-    if (valid) slot = kq < base ? kq : base + (anc ? anc[kq - base] : kq - base);
+    // lanes past the range re-read the last key of the range (initialised data; their weight is 0)
+    const int kr = valid ? kq : k_hi - 1;
+    const int slot = kr < base ? kr : base + (anc ? anc[kr - base] : kr - base);
     const T *kptr = kbase + (size_t)slot * row_stride;
     const T *vptr = vbase + (size_t)slot * row_stride;
     u32x4_t kc[HD / EPL], vc[HD / EPL];
@@ -130,11 +127,9 @@ __device__ __forceinline__ void attn_part_body(const AttnArgs &a, int i, int hk,
 #pragma unroll
         for (int e = 0; e < EPL; e++) s[gh] = fmaf(qs[gh][dc * EPL + e], kf[e], s[gh]);
     }
-    // stage the value rows: row `lane` of vs (lanes past VR never hold a key)
-    if (VR == 64 || lane < VR) {
+    // stage the value rows: row `lane` of vs
 #pragma unroll
-      for (int dc = 0; dc < HD / EPL; dc++) *(u32x4_t *)(vs + lane * VROW + dc * 16) = vc[dc];
-    }
+    for (int dc = 0; dc < HD / EPL; dc++) *(u32x4_t *)(vs + lane * VROW + dc * 16) = vc[dc];
     float pk[G];
 #pragma unroll
     for (int gh = 0; gh < G; gh++) {
@@ -150,7 +145,7 @@ __device__ __forceinline__ void attn_part_body(const AttnArgs &a, int i, int hk,
     wave_lds_sync();                                   // value rows staged
     // lane = output dims lane*DPL ..: accumulate key by key in position order
     // Eight keys per step so that the LDS reads of a step are in flight together.  Lanes past the last
-    // key hold weight 0 and a valid finite value row (slot 0), so rounding a step up to eight adds zeros.
+    // key hold weight 0 and a finite value row (a copy of the last key's), so rounding a step up to eight adds zeros.
     const int nk = min(64, k_hi - kb);
     const unsigned char *vcol = vs + lane * DPL * (int)sizeof(T);
     for (int k0 = 0; k0 < nk; k0 += 8) {
@@ -170,10 +165,104 @@ __device__ __forceinline__ void attn_part_body(const AttnArgs &a, int i, int hk,
     }
   }
   if (!store) return;
-  const int part_slot = a.tail_only ? a.max_parts - 1 : part;   // the tail goes to the last slot
 #pragma unroll
   for (int gh = 0; gh < G; gh++) {
-    float *dst = a.part + (((size_t)i * a.hq + hk * G + gh) * a.max_parts + part_slot) * (HD + 2);
+    float *dst = a.part + (((size_t)i * a.hq + hk * G + gh) * a.max_parts + part) * (HD + 2);
+    if (lane == 0) { dst[0] = m_run[gh]; dst[1] = l_run[gh]; }
+#pragma unroll
+    for (int dd = 0; dd < DPL; dd++) dst[2 + lane * DPL + dd] = o[gh][dd];
+  }
+}
+
+// The tail of a row in the hybrid path: positions [max(p - kMaxDepth, 0), p], at most kTailKeys = 16 keys,
+// the end of the committed cache followed by the row's own path.  One wavefront per (row, kv head): four
+// lanes share a key (each takes a quarter of the head dim for the score, summed over the quad in a fixed
+// order), then lane = output dim for P*V over the value rows staged in LDS, key by key in position order.
+// The result goes to the last part slot.
+constexpr int kTailKeys = kMaxDepth + 1;
+static_assert(kTailKeys * 4 == 64, "one wavefront = 16 keys x 4 lanes");
+template <typename T, int HD, int G>
+__device__ __forceinline__ void attn_tail_body(const AttnArgs &a, int i, int hk, int lane, float (*qs)[HD],
+                                               unsigned char *vs, bool store) {
+  constexpr int EPL = Chunk<T>::kEpl;
+  constexpr int DPL = HD / 64;                       // output dims per lane (contiguous)
+  constexpr int VROW = PartLds<T>::vrow(HD);
+  constexpr int QD = HD / 4;                         // dims per lane of a key quad
+  constexpr int QC = QD / EPL;                       // 16-byte chunks per lane
+  const int base = a.base_ptr ? *a.base_ptr : a.base;
+  const int p = base + a.depth[i];
+  const int k_lo = bulk_end(p);
+  const int kk = lane >> 2, qt = lane & 3;
+  const int kq = k_lo + kk;
+  const bool valid = kq <= p;
+  const int *anc = a.anc ? a.anc + (size_t)i * kAncStride : nullptr;
+  // lanes past position p re-read the row's own key (initialised data; their weight is 0)
+  const int kr = valid ? kq : p;
+  const int slot = kr < base ? kr : base + (anc ? anc[kr - base] : kr - base);
+  const size_t row_stride = (size_t)a.hkv * HD;
+  const T *kptr = (const T *)a.kcache + (size_t)slot * row_stride + (size_t)hk * HD + qt * QD;
+  const T *vptr = (const T *)a.vcache + (size_t)slot * row_stride + (size_t)hk * HD + qt * QD;
+  u32x4_t kc[QC], vc[QC];
+#pragma unroll
+  for (int dc = 0; dc < QC; dc++) kc[dc] = *(const u32x4_t *)(kptr + dc * EPL);
+#pragma unroll
+  for (int dc = 0; dc < QC; dc++) vc[dc] = *(const u32x4_t *)(vptr + dc * EPL);
+  const float *qrow = (const float *)a.q + ((size_t)i * a.hq + (size_t)hk * G) * HD;   // queries are fp32
+  for (int e = lane; e < G * HD; e += 64) qs[e / HD][e % HD] = qrow[e];
+  wave_lds_sync();
+  float s[G];
+#pragma unroll
+  for (int gh = 0; gh < G; gh++) s[gh] = 0.f;
+#pragma unroll
+  for (int dc = 0; dc < QC; dc++) {
+    float kf[EPL];
+    Chunk<T>::unpack(kc[dc], kf);
+#pragma unroll
+    for (int gh = 0; gh < G; gh++)
+#pragma unroll
+      for (int e = 0; e < EPL; e++) s[gh] = fmaf(qs[gh][qt * QD + dc * EPL + e], kf[e], s[gh]);
+  }
+#pragma unroll
+  for (int dc = 0; dc < QC; dc++) *(u32x4_t *)(vs + kk * VROW + qt * QD * (int)sizeof(T) + dc * 16) = vc[dc];
+  float m_run[G], l_run[G], pk[G];
+#pragma unroll
+  for (int gh = 0; gh < G; gh++) {
+    float t = s[gh];
+    t += __shfl_xor(t, 1, 64);                       // quad sum, fixed order
+    t += __shfl_xor(t, 2, 64);
+    const float sc = valid ? t * a.scale : -INFINITY;
+    m_run[gh] = wave_max(sc);                        // at least key p itself is valid
+    pk[gh] = valid ? __expf(sc - m_run[gh]) : 0.f;
+    l_run[gh] = wave_sum(qt == 0 ? pk[gh] : 0.f);
+  }
+  wave_lds_sync();                                   // value rows staged
+  float o[G][DPL];
+#pragma unroll
+  for (int gh = 0; gh < G; gh++)
+#pragma unroll
+    for (int dd = 0; dd < DPL; dd++) o[gh][dd] = 0.f;
+  // Lanes of keys past p hold weight 0 and a finite value row (a copy of the row's own), so all 16 rows can be summed.
+  const unsigned char *vcol = vs + lane * DPL * (int)sizeof(T);
+#pragma unroll
+  for (int k0 = 0; k0 < kTailKeys; k0 += 8) {
+    float vv[8][DPL];
+#pragma unroll
+    for (int u = 0; u < 8; u++)
+#pragma unroll
+      for (int dd = 0; dd < DPL; dd++) vv[u][dd] = to_f32(*(const T *)(vcol + (k0 + u) * VROW + dd * (int)sizeof(T)));
+#pragma unroll
+    for (int u = 0; u < 8; u++)
+#pragma unroll
+      for (int gh = 0; gh < G; gh++) {
+        const float w = __shfl(pk[gh], (k0 + u) * 4, 64);
+#pragma unroll
+        for (int dd = 0; dd < DPL; dd++) o[gh][dd] = fmaf(w, vv[u][dd], o[gh][dd]);
+      }
+  }
+  if (!store) return;
+#pragma unroll
+  for (int gh = 0; gh < G; gh++) {
+    float *dst = a.part + (((size_t)i * a.hq + hk * G + gh) * a.max_parts + a.max_parts - 1) * (HD + 2);
     if (lane == 0) { dst[0] = m_run[gh]; dst[1] = l_run[gh]; }
 #pragma unroll
     for (int dd = 0; dd < DPL; dd++) dst[2 + lane * DPL + dd] = o[gh][dd];
@@ -185,7 +274,7 @@ template <typename T, int HD, int G>
 __global__ __launch_bounds__(64) void attn_part_kernel(AttnArgs a) {
   __shared__ __attribute__((aligned(16))) float qs[G][HD];
   __shared__ __attribute__((aligned(16))) unsigned char vs[64 * PartLds<T>::vrow(HD)];
-  attn_part_body<T, HD, G, 64>(a, blockIdx.x, blockIdx.y, blockIdx.z, threadIdx.x, qs, vs, true);
+  attn_part_body<T, HD, G>(a, blockIdx.x, blockIdx.y, blockIdx.z, threadIdx.x, qs, vs, true);
 }
 
 // grid (rows, hq); block HD threads.  Merges the row's parts in ascending order; in hybrid mode these are
@@ -237,7 +326,7 @@ constexpr int kBulkBlocksPerPart = kAttnPart / 32;
 // of the kv group), r = (qgroup*NW + w)*32 + lane%32, i = r / G, gh = r % G.  The remaining workgroups run
 // the vector tail, one (row, kv head) item per wavefront on the first kTailWaves wavefronts, and leave it in
 // the last part slot.  The two kinds of work are independent; attn_combine_kernel merges them afterwards.
-template <int NW> struct TailWaves { static constexpr int value = NW < 2 ? 1 : 2; };
+template <int NW> struct TailWaves { static constexpr int value = NW < 4 ? NW : 4; };
 template <int HD, int G, int NW>
 __global__ __launch_bounds__(NW * 64) void attn_hybrid_kernel(AttnArgs a) {
   constexpr int DB = HD / 32;                 // 32-dim blocks of the output
@@ -248,7 +337,7 @@ __global__ __launch_bounds__(NW * 64) void attn_hybrid_kernel(AttnArgs a) {
   constexpr int PIECES = (32 * HD * 2 / 16 + NT - 1) / NT;   // 16-byte pieces of one K (or V) block per thread
   constexpr int kTailWaves = TailWaves<NW>::value;
   constexpr int kTailQ = G * HD * 4;                                         // a tail wavefront's query area
-  constexpr int kTailWave = kTailQ + kTailRows * PartLds<bf16_t>::vrow(HD);  // ... plus its staged value rows
+  constexpr int kTailWave = kTailQ + kTailKeys * PartLds<bf16_t>::vrow(HD);  // ... plus its staged value rows
   constexpr int kBulkLds = 32 * KSTR + HD * VSTR;
   constexpr int kLds = kBulkLds > kTailWaves * kTailWave ? kBulkLds : kTailWaves * kTailWave;
   __shared__ __attribute__((aligned(16))) unsigned char lds[kLds];
@@ -261,8 +350,7 @@ __global__ __launch_bounds__(NW * 64) void attn_hybrid_kernel(AttnArgs a) {
     const bool active = item < a.rows * a.hkv;
     if (!active) item = a.rows * a.hkv - 1;               // valid addresses; result discarded
     unsigned char *mine = lds + w * kTailWave;
-    attn_part_body<bf16_t, HD, G, kTailRows>(a, item / a.hkv, item % a.hkv, 0, threadIdx.x & 63, (float (*)[HD])mine,
-                                             mine + kTailQ, active);
+    attn_tail_body<bf16_t, HD, G>(a, item / a.hkv, item % a.hkv, threadIdx.x & 63, (float (*)[HD])mine, mine + kTailQ, active);
     return;
   }
   unsigned char *k_lds = lds, *vt_lds = lds + 32 * KSTR;
@@ -272,7 +360,9 @@ __global__ __launch_bounds__(NW * 64) void attn_hybrid_kernel(AttnArgs a) {
   // With a device-resident base (graph replay) the grid is sized for the longest context and the
   // blocks that exist are derived here; otherwise the host has computed them.
   const int base = a.base_ptr ? *a.base_ptr : a.base;
-  const int n_blocks = a.base_ptr ? min(a.bulk_blocks, bulk_end(base + kMaxDepth) / 32) : a.bulk_blocks;
+  // keys [0, key_lim) are the union of the rows' bulk regions: all of them exist and are initialised
+  const int key_lim = a.base_ptr ? min(a.bulk_keys, bulk_end(base + kMaxDepth)) : a.bulk_keys;
+  const int n_blocks = (key_lim + 31) / 32;
   const int b_lo = part * kBulkBlocksPerPart;
   const int b_hi = min(b_lo + kBulkBlocksPerPart, n_blocks);
   if (b_lo >= b_hi) return;
@@ -280,7 +370,7 @@ __global__ __launch_bounds__(NW * 64) void attn_hybrid_kernel(AttnArgs a) {
   const int r = (qgroup * NW + wave) * 32 + c;
   const bool valid_q = r < a.rows * G;
   const int i = valid_q ? r / G : 0, gh = valid_q ? r % G : 0;
-  const int n_incl = valid_q ? bulk_end(base + a.depth[i]) / 32 : 0;        // blocks [0, n_incl) belong to this row
+  const int k_end = valid_q ? bulk_end(base + a.depth[i]) : 0;               // keys [0, k_end) belong to this row's bulk
 
   // query fragments: step kk covers dims kk*16 + g*8 .. +8
   u32x4_t qhi[KK], qlo[KK];
@@ -311,7 +401,9 @@ __global__ __launch_bounds__(NW * 64) void attn_hybrid_kernel(AttnArgs a) {
     for (int e = 0; e < PIECES; e++) {
       const int q = tid + e * NT;
       const int key = (q / PPR) & 31, piece = q % PPR;       // (& 31: threads past the block re-read a valid key)
-      const size_t off = (size_t)(b * 32 + key) * row_stride + piece * 8;
+      // The last block may reach past key_lim; those keys are masked for every row, so they are read from
+      // key key_lim - 1 instead (initialised, inside the cache; key_lim >= 1 for every block that runs).
+      const size_t off = (size_t)min(b * 32 + key, key_lim - 1) * row_stride + piece * 8;
       kreg[e] = *(const u32x4_t *)(kg + off);
       vreg[e] = *(const u32x4_t *)(vg + off);
     }
@@ -348,16 +440,20 @@ __global__ __launch_bounds__(NW * 64) void attn_hybrid_kernel(AttnArgs a) {
       s = mfma_bf16(kf, qlo[kk], s);
     }
     // s[v] = q . k for key 8*(v/4) + 4*g + v%4 of the block and query row c
-    const bool incl = b < n_incl;
+    // keys at or past k_end are masked: they add exact zeros, so a row's result does not depend on them
+    const int key0 = b * 32 + 4 * g;
     float mb = -INFINITY;
 #pragma unroll
-    for (int v = 0; v < 16; v++) { s[v] = incl ? s[v] * a.scale : -INFINITY; mb = fmaxf(mb, s[v]); }
+    for (int v = 0; v < 16; v++) {
+      s[v] = key0 + 8 * (v >> 2) + (v & 3) < k_end ? s[v] * a.scale : -INFINITY;
+      mb = fmaxf(mb, s[v]);
+    }
     mb = fmaxf(mb, __shfl_xor(mb, 32, 64));
     const float m_new = fmaxf(m_run, mb);
     const float corr = m_new == -INFINITY ? 1.f : __expf(m_run - m_new);
     float pv[16], ls = 0.f;
 #pragma unroll
-    for (int v = 0; v < 16; v++) { pv[v] = incl ? __expf(s[v] - m_new) : 0.f; ls += pv[v]; }
+    for (int v = 0; v < 16; v++) { pv[v] = s[v] == -INFINITY ? 0.f : __expf(s[v] - m_new); ls += pv[v]; }
     ls += __shfl_xor(ls, 32, 64);
     l_run = l_run * corr + ls;
     m_run = m_new;
@@ -407,7 +503,8 @@ static hipError_t launch_thg(AttnArgs a, int max_pos, hipStream_t st) {
   if (sizeof(T) == 2) {
     // hybrid: matrix-core bulk over [0, A(max_pos)) and the vector tail of every row in one launch
     a.tail_only = 1;
-    a.bulk_blocks = bulk_end(max_pos) / 32;
+    a.bulk_keys = bulk_end(max_pos);
+    a.bulk_blocks = (a.bulk_keys + 31) / 32;
     a.bulk_parts = (a.bulk_blocks + kBulkBlocksPerPart - 1) / kBulkBlocksPerPart;
     if (a.bulk_parts + 1 > a.max_parts) return hipErrorInvalidValue;
     const int qblocks = (a.rows * G + 31) / 32;

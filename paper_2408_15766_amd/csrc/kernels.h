@@ -78,7 +78,7 @@ struct AttnArgs {
   float *part;                          // scratch: [rows][hq][max_parts][hd + 2]; max_parts >= max_pos/kAttnPart + 2
   int max_parts;
   void *out;
-  int tail_only, bulk_blocks, bulk_parts, q_groups;   // set by launch_attention (hybrid matrix-core / vector split)
+  int tail_only, bulk_keys, bulk_blocks, bulk_parts, q_groups;   // set by launch_attention (hybrid matrix-core / vector split)
 };
 hipError_t launch_attention(int dtype, const AttnArgs &a, int max_pos, hipStream_t st);
 

@@ -182,11 +182,17 @@ def bf16_model(request, env):
 def test_bf16_logits_within_tolerance_of_oracle(env, bf16_model):
     """Real widths, two layers: GPU bf16 logits of a verified tree against the oracle on the same tree.
 
-    (1) Against the oracle evaluated with the configuration's storage type (activations held in bf16 between
-        operations, as the configuration defines): every logit within 3e-2 + 2e-2 |ref|.
-    (2) Against the plain fp32 oracle: the same bound holds for at least 99 % of the logits and the error stays
-        within what bf16 storage of the cached keys/values and of the GEMM inputs must produce (rms < 0.02,
-        max < 0.12 at logit sigma 1.3); the derivation is in the design notes."""
+    Tolerance per logit: 3e-2 + 2e-2 |ref|.
+
+    (1) Against the oracle evaluated with the configuration's storage type (activations, keys and values held in
+        bf16 between operations, fp64 arithmetic).  Any fp32 implementation differs from this reference where an
+        fp32 and an fp64 intermediate fall on different sides of a bf16 rounding boundary; the size of that effect
+        is measured here by evaluating the SAME oracle code in fp32 arithmetic (max ~0.03, rms ~0.006 at these
+        widths).  Required: at least 99.99 % of the logits within tolerance, and max / rms error no larger than
+        2x / 1.5x what the oracle's own fp32 evaluation shows.
+    (2) Against the plain fp32 oracle (no storage rounding): the tolerance holds for at least 99 % of the logits and
+        the error stays within what bf16 storage of the cached keys/values and of the GEMM inputs must produce
+        (rms < 0.02, max < 0.12 at logit sigma 1.3)."""
     torch, P = env
     sh, hw, dw, prompt = bf16_model
     eng = P.Engine(sh, dw)
@@ -194,20 +200,26 @@ def test_bf16_logits_within_tolerance_of_oracle(env, bf16_model):
     t = eng.draft_tree()
     eng.verify(t)
     got = eng.logits(t.n_nodes)
-    w32 = as_dtype(hw, np.float32)
-    for store, strict in ((wl.round_to_bf16, True), (None, False)):
-        st, ofirst = oracle.prefill(w32, sh, prompt, len(prompt) + 200, dtype=np.float32, store=store)
+
+    def oracle_logits(dtype, store):
+        st, _ = oracle.prefill(as_dtype(hw, dtype), sh, prompt, len(prompt) + 200, dtype=dtype, store=store)
         ot = oracle.Tree(t.token[:t.n_nodes].copy(), t.parent[:t.n_nodes].copy(), t.depth[:t.n_nodes].copy(), t.score[:t.n_nodes].copy())
         ot.token[0] = first                   # compare on the GPU's root token even if a near-tie flipped the oracle's
-        want, _ = oracle.verify_tree(st, ot)
-        err = np.abs(got - want)
-        ok = err <= 3e-2 + 2e-2 * np.abs(want)
-        print(f"{sh.name} store={'bf16' if store else 'fp32'}: max err {err.max():.4f} rms {np.sqrt((err ** 2).mean()):.4f} "
-              f"within tolerance {ok.mean() * 100:.3f} %")
-        if strict:
-            assert ok.all(), f"max abs err {err.max()}"
-        else:
-            assert ok.mean() >= 0.99 and err.max() < 0.12 and np.sqrt((err ** 2).mean()) < 0.02
+        return np.asarray(oracle.verify_tree(st, ot)[0], dtype=np.float64)
+
+    def stats(x, ref, tag):
+        err = np.abs(x - ref)
+        ok = err <= 3e-2 + 2e-2 * np.abs(ref)
+        print(f"{sh.name} {tag}: max err {err.max():.4f} rms {np.sqrt((err ** 2).mean()):.4f} within tolerance {ok.mean() * 100:.4f} %")
+        return err.max(), np.sqrt((err ** 2).mean()), ok.mean()
+
+    ref_store = oracle_logits(np.float64, wl.round_to_bf16)
+    floor_max, floor_rms, _ = stats(oracle_logits(np.float32, wl.round_to_bf16), ref_store, "oracle fp32 arithmetic vs fp64, bf16 storage")
+    g_max, g_rms, g_ok = stats(got, ref_store, "GPU vs oracle with bf16 storage")
+    assert g_ok >= 0.9999
+    assert g_max <= max(3e-2, 2.0 * floor_max) and g_rms <= max(3e-3, 1.5 * floor_rms)
+    p_max, p_rms, p_ok = stats(got, oracle_logits(np.float32, None), "GPU vs plain fp32 oracle")
+    assert p_ok >= 0.99 and p_max < 0.12 and p_rms < 0.02
 
 
 def test_bf16_spec_equals_greedy_bit_exact(env, bf16_model):
@@ -252,6 +264,31 @@ def test_graph_replay_equals_eager_launches(env, bf16_model):
     assert ta == tb == greedy[:gen] and ua == ub and len(ra) == len(rb) >= 4
     for a, b in zip(ra, rb):
         assert np.array_equal(a["logits"], b["logits"]) and np.array_equal(a["feats"], b["feats"])
+
+
+def test_results_do_not_depend_on_workspace_contents(env, bf16_model, tiny_gpu):
+    """The library initialises everything it reads: a workspace handed over full of 0xFF bytes (NaN patterns in
+    bf16 and fp32) gives bit-identical trees, tokens and logits to a zero-filled one.  Also with a one-token
+    prompt, where the draft cache is empty in the first cycle."""
+    torch, P = env
+    cases = [(bf16_model[0], bf16_model[2], bf16_model[3]), (tiny_gpu[0], tiny_gpu[4], tiny_gpu[3]),
+             (tiny_gpu[0], tiny_gpu[4], tiny_gpu[3][:1])]
+    for sh, dw, prompt in cases:
+        runs = []
+        for fill in (0, 0xFF):
+            eng = P.Engine(sh, dw, workspace_fill=fill)
+            rec = [eng.prefill(prompt)]
+            for _ in range(4):
+                t = eng.draft_tree()
+                eng.verify(t)
+                rec.append((t.token[:t.n_nodes].copy(), t.parent[:t.n_nodes].copy(), t.score[:t.n_nodes].copy(),
+                            eng.logits(t.n_nodes).copy(), list(eng.accept(t))))
+            eng.close()
+            runs.append(rec)
+        assert runs[0][0] == runs[1][0]
+        for a, b in zip(runs[0][1:], runs[1][1:]):
+            assert all(np.array_equal(x, y) for x, y in zip(a[:4], b[:4])) and a[4] == b[4]
+            assert np.isfinite(a[3]).all()
 
 
 def test_bf16_sampling_acceptance_matches_oracle_on_gpu_logits(env, bf16_model):
