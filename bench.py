@@ -23,7 +23,7 @@ if ROOT not in sys.path:
 HBM_PEAK_GBPS = 8000.0
 # HBM bytes per GEMM launch (fetch + write) measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by a
 # plain-copy calibration: see profiles/traffic_gemm_stream_<workload>.txt.  None where not measured.
-MEASURED_TRAFFIC_BYTES_PER_LAUNCH = {"llama2-7b": 114.5e6}
+MEASURED_TRAFFIC_BYTES_PER_LAUNCH = {"llama2-7b": 113.5e6}
 
 
 def parse():
@@ -147,7 +147,7 @@ def main():
     kv_read = n_mid * by["kv_bytes_per_token"]
     kv_write = sh.tree_total * by["kv_bytes_per_token"]
     out = {
-        "metric": "tokens/s (bs=1, T=0)", "value": tokens_per_s, "unit": "tokens/s", "n_gpus": 1, "steps": a.steps,
+        "metric": f"tokens/s (bs=1, T={sh.temperature:g})", "value": tokens_per_s, "unit": "tokens/s", "n_gpus": 1, "steps": a.steps,
         "warmup": a.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": sh.dtype, "data": "synthetic",
         "config": {"workload": f"{sh.name} shape, random init N(0,0.02), prompt {sh.prompt_len} uniform tokens, "
@@ -175,14 +175,17 @@ def main():
                             "verify_hbm_frac": (by["verify_weights"] + kv_read + kv_write) / (verify_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS})
             else:
                 n_launch = cnt[4] / a.steps                      # GEMM launches per verify
-                avg_ms = ms[4] / max(cnt[4], 1)
+                pair_ms = ms[6] / max(cnt[6], 1)                 # what an empty event pair measures
+                raw_ms = ms[4] / max(cnt[4], 1)
+                avg_ms = raw_ms - pair_ms
                 bytes_per_launch = by["verify_weights"] / n_launch
                 achieved = bytes_per_launch / (avg_ms * 1e-3) / 1e9
                 out["roofline"] = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                                    "frac": achieved / HBM_PEAK_GBPS,
                                    "traffic": MEASURED_TRAFFIC_BYTES_PER_LAUNCH.get(a.config) if not a.layers else None,
                                    "kernel": "gemm_stream_kernel (verify launches)", "launches_per_step": n_launch,
-                                   "avg_launch_ms": avg_ms, "algorithmic_bytes_per_launch": bytes_per_launch}
+                                   "avg_launch_ms": avg_ms, "event_interval_ms": raw_ms, "empty_event_pair_ms": pair_ms,
+                                   "algorithmic_bytes_per_launch": bytes_per_launch}
     if not a.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl.BY_NAME[a.config])
     print(json.dumps(out))

@@ -184,7 +184,10 @@ int spec_set_graphs(spec_ctx *ctx, int32_t enable);
  * (perturbs the pipeline; use in a separate pass).  spec_get_profile fills
  * HOST arrays of 8 doubles / 8 int64 and resets the counters:
  *   [0] draft ms   [1] verify ms   [2] accept ms   [3] prefill ms
- *   [4] GEMM ms inside verify      [5] GEMM ms inside draft   [6],[7] reserved
+ *   [4] GEMM ms inside verify      [5] GEMM ms inside draft
+ *   [6] level 2 calibration: one event pair per verify with nothing between its two records, taken
+ *       while the stream is busy (what the event mechanism itself adds to every interval of [4], [5])
+ *   [7] reserved
  * counts[i] = number of intervals summed into ms[i]. */
 int spec_set_profile(spec_ctx *ctx, int32_t level);
 int spec_get_profile(spec_ctx *ctx, double *ms, int64_t *counts);

@@ -328,7 +328,7 @@ constexpr int kBulkBlocksPerPart = kAttnPart / 32;
 // the last part slot.  The two kinds of work are independent; attn_combine_kernel merges them afterwards.
 template <int NW> struct TailWaves { static constexpr int value = NW < 4 ? NW : 4; };
 template <int HD, int G, int NW>
-__global__ __launch_bounds__(NW * 64) void attn_hybrid_kernel(AttnArgs a) {
+__global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_hybrid_kernel(AttnArgs a) {
   constexpr int DB = HD / 32;                 // 32-dim blocks of the output
   constexpr int KK = HD / 16;                 // MFMA steps of q.k
   constexpr int KSTR = HD * 2 + 16;           // LDS bytes per key row (+16: conflict-free b128 reads)
@@ -372,6 +372,24 @@ __global__ __launch_bounds__(NW * 64) void attn_hybrid_kernel(AttnArgs a) {
   const int i = valid_q ? r / G : 0, gh = valid_q ? r % G : 0;
   const int k_end = valid_q ? bulk_end(base + a.depth[i]) : 0;               // keys [0, k_end) belong to this row's bulk
 
+  const size_t row_stride = (size_t)a.hkv * HD;              // elements between consecutive cache slots
+  const bf16_t *kg = (const bf16_t *)a.kcache + (size_t)hk * HD;
+  const bf16_t *vg = (const bf16_t *)a.vcache + (size_t)hk * HD;
+  constexpr int PPR = HD * 2 / 16;                           // pieces per key row
+  u32x4_t kreg[PIECES], vreg[PIECES];
+  auto prefetch = [&](int b) {
+#pragma unroll
+    for (int e = 0; e < PIECES; e++) {
+      const int q = tid + e * NT;
+      const int key = (q / PPR) & 31, piece = q % PPR;       // (& 31: threads past the block re-read a valid key)
+      // The last block may reach past key_lim; those keys are masked for every row, so they are read from
+      // key key_lim - 1 instead (initialised, inside the cache; key_lim >= 1 for every block that runs).
+      const size_t off = (size_t)min(b * 32 + key, key_lim - 1) * row_stride + piece * 8;
+      kreg[e] = *(const u32x4_t *)(kg + off);
+      vreg[e] = *(const u32x4_t *)(vg + off);
+    }
+  };
+  prefetch(b_lo);                                            // first K/V block in flight while the queries load
   // query fragments: step kk covers dims kk*16 + g*8 .. +8
   u32x4_t qhi[KK], qlo[KK];
   {
@@ -391,23 +409,6 @@ __global__ __launch_bounds__(NW * 64) void attn_hybrid_kernel(AttnArgs a) {
     for (int v = 0; v < 16; v++) o[db][v] = 0.f;
   float m_run = -INFINITY, l_run = 0.f;
 
-  const size_t row_stride = (size_t)a.hkv * HD;              // elements between consecutive cache slots
-  const bf16_t *kg = (const bf16_t *)a.kcache + (size_t)hk * HD;
-  const bf16_t *vg = (const bf16_t *)a.vcache + (size_t)hk * HD;
-  constexpr int PPR = HD * 2 / 16;                           // pieces per key row
-  u32x4_t kreg[PIECES], vreg[PIECES];
-  auto prefetch = [&](int b) {
-#pragma unroll
-    for (int e = 0; e < PIECES; e++) {
-      const int q = tid + e * NT;
-      const int key = (q / PPR) & 31, piece = q % PPR;       // (& 31: threads past the block re-read a valid key)
-      // The last block may reach past key_lim; those keys are masked for every row, so they are read from
-      // key key_lim - 1 instead (initialised, inside the cache; key_lim >= 1 for every block that runs).
-      const size_t off = (size_t)min(b * 32 + key, key_lim - 1) * row_stride + piece * 8;
-      kreg[e] = *(const u32x4_t *)(kg + off);
-      vreg[e] = *(const u32x4_t *)(vg + off);
-    }
-  };
   auto stage = [&]() {
 #pragma unroll
     for (int e = 0; e < PIECES; e++) {
@@ -423,7 +424,6 @@ __global__ __launch_bounds__(NW * 64) void attn_hybrid_kernel(AttnArgs a) {
     }
   };
 
-  prefetch(b_lo);
   for (int b = b_lo; b < b_hi; b++) {
     __syncthreads();                                         // every wave is done reading the previous block
     stage();
