@@ -278,23 +278,50 @@ __global__ __launch_bounds__(64) void attn_part_kernel(AttnArgs a) {
 }
 
 // grid (rows, hq); block HD threads.  Merges the row's parts in ascending order; in hybrid mode these are
-// the bulk parts followed by the tail (kept in the last slot).
+// the bulk parts followed by the tail (kept in the last slot).  The (max, sum) pairs of up to kCombineChunk
+// parts are fetched by one thread each and turned into weights in LDS, so that the per-dim pass issues
+// independent, coalesced loads; the sums themselves run in ascending part order.
+constexpr int kCombineChunk = 64;
 template <typename T, int HD>
-__global__ void attn_combine_kernel(AttnArgs a) {
+__global__ __launch_bounds__(HD) void attn_combine_kernel(AttnArgs a) {
+  __shared__ float pm[kCombineChunk], pl[kCombineChunk];
+  __shared__ float red[2];
   const int i = blockIdx.x, h = blockIdx.y, d = threadIdx.x;
   const int p = (a.base_ptr ? *a.base_ptr : a.base) + a.depth[i];
   const int n_front = a.tail_only ? (bulk_end(p) + kAttnPart - 1) / kAttnPart : p / kAttnPart + 1;
   const int n_parts = n_front + (a.tail_only ? 1 : 0);
   const float *src = a.part + ((size_t)i * a.hq + h) * a.max_parts * (HD + 2);
   auto slot = [&](int t) { return (size_t)(t < n_front ? t : a.max_parts - 1) * (HD + 2); };
+  // pass 1: the row's maximum
   float m = -INFINITY;
-  for (int t = 0; t < n_parts; t++) m = fmaxf(m, src[slot(t)]);
+  for (int t = d; t < n_parts; t += HD) m = fmaxf(m, src[slot(t)]);
+  m = wave_max(m);
+  if (HD > 64) {
+    if ((d & 63) == 0) red[d >> 6] = m;
+    __syncthreads();
+    m = fmaxf(red[0], red[1]);
+  }
+  // pass 2: chunks of parts; weights once per part, then every thread adds its dim in ascending order
   float l = 0.f, o = 0.f;
-  for (int t = 0; t < n_parts; t++) {
-    const float *s = src + slot(t);
-    const float w = __expf(s[0] - m);
-    l += s[1] * w;
-    o += s[2 + d] * w;
+  for (int t0 = 0; t0 < n_parts; t0 += kCombineChunk) {
+    const int nt = min(kCombineChunk, n_parts - t0);
+    __syncthreads();
+    if (d < nt) {
+      const float *sp = src + slot(t0 + d);
+      const float w = __expf(sp[0] - m);
+      pm[d] = w; pl[d] = sp[1] * w;
+    }
+    __syncthreads();
+    int t = 0;
+    for (; t + 4 <= nt; t += 4) {
+      const float v0 = src[slot(t0 + t) + 2 + d], v1 = src[slot(t0 + t + 1) + 2 + d];
+      const float v2 = src[slot(t0 + t + 2) + 2 + d], v3 = src[slot(t0 + t + 3) + 2 + d];
+      l += pl[t]; o += v0 * pm[t];
+      l += pl[t + 1]; o += v1 * pm[t + 1];
+      l += pl[t + 2]; o += v2 * pm[t + 2];
+      l += pl[t + 3]; o += v3 * pm[t + 3];
+    }
+    for (; t < nt; t++) { l += pl[t]; o += src[slot(t0 + t) + 2 + d] * pm[t]; }
   }
   ((T *)a.out)[((size_t)i * a.hq + h) * HD + d] = from_f32<T>(o / l);
 }
@@ -338,7 +365,8 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2, 2)))
   constexpr int kTailWaves = TailWaves<NW>::value;
   constexpr int kTailQ = G * HD * 4;                                         // a tail wavefront's query area
   constexpr int kTailWave = kTailQ + kTailKeys * PartLds<bf16_t>::vrow(HD);  // ... plus its staged value rows
-  constexpr int kBulkLds = 32 * KSTR + HD * VSTR;
+  constexpr int kBulkBuf = 32 * KSTR + HD * VSTR;                            // one staged K block + V^T block
+  constexpr int kBulkLds = 2 * kBulkBuf;                                     // double-buffered
   constexpr int kLds = kBulkLds > kTailWaves * kTailWave ? kBulkLds : kTailWaves * kTailWave;
   __shared__ __attribute__((aligned(16))) unsigned char lds[kLds];
 
@@ -353,7 +381,6 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2, 2)))
     attn_tail_body<bf16_t, HD, G>(a, item / a.hkv, item % a.hkv, threadIdx.x & 63, (float (*)[HD])mine, mine + kTailQ, active);
     return;
   }
-  unsigned char *k_lds = lds, *vt_lds = lds + 32 * KSTR;
   const int part = (int)blockIdx.x % a.bulk_parts, hk = ((int)blockIdx.x / a.bulk_parts) % a.hkv;
   const int qgroup = (int)blockIdx.x / (a.bulk_parts * a.hkv);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, c = lane & 31, g = lane >> 5;
@@ -409,7 +436,8 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2, 2)))
     for (int v = 0; v < 16; v++) o[db][v] = 0.f;
   float m_run = -INFINITY, l_run = 0.f;
 
-  auto stage = [&]() {
+  auto stage = [&](int buf) {
+    unsigned char *k_lds = lds + buf * kBulkBuf, *vt_lds = k_lds + 32 * KSTR;
 #pragma unroll
     for (int e = 0; e < PIECES; e++) {
       const int q = tid + e * NT;
@@ -424,11 +452,15 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2, 2)))
     }
   };
 
+  // K/V blocks alternate between two LDS buffers: block b+1 is staged (from the registers its global loads
+  // filled during block b-1's compute) between the two matrix-core phases of block b, and the loads of
+  // block b+2 are issued right after; one barrier per block.
+  stage(0);
+  __syncthreads();
+  if (b_lo + 1 < b_hi) prefetch(b_lo + 1);
   for (int b = b_lo; b < b_hi; b++) {
-    __syncthreads();                                         // every wave is done reading the previous block
-    stage();
-    __syncthreads();
-    if (b + 1 < b_hi) prefetch(b + 1);
+    const int cur = (b - b_lo) & 1;
+    const unsigned char *k_lds = lds + cur * kBulkBuf, *vt_lds = k_lds + 32 * KSTR;
 
     f32x16_t s;
 #pragma unroll
@@ -461,6 +493,10 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2, 2)))
     for (int db = 0; db < DB; db++)
 #pragma unroll
       for (int v = 0; v < 16; v++) o[db][v] *= corr;
+    if (b + 1 < b_hi) {
+      stage(cur ^ 1);                                        // every wave left that buffer at the last barrier
+      if (b + 2 < b_hi) prefetch(b + 2);
+    }
     // O^T += V^T P^T over two 16-key steps; step t uses the lane's own values v = 8t .. 8t+7,
     // i.e. keys 16t + 8*(e/4) + 4g + e%4, and V^T supplies the same keys per dim.
 #pragma unroll
@@ -479,6 +515,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2, 2)))
         o[db] = mfma_bf16(vf, plo, o[db]);
       }
     }
+    __syncthreads();                                         // block b+1 staged; everyone is done with block b
   }
   if (!valid_q) return;
   float *dst = a.part + (((size_t)i * a.hq + hk * G + gh) * a.max_parts + part) * (HD + 2);
