@@ -33,6 +33,9 @@ def parse():
     ap.add_argument("--warmup", type=int, default=4)
     ap.add_argument("--config", default="llama2-7b", help="workload name (see workload.CONFIGS)")
     ap.add_argument("--layers", type=int, default=0, help="override the number of target layers (0 = the config's)")
+    ap.add_argument("--forced-accept", type=int, default=4,
+                    help="draft tokens accepted per cycle in the teacher-forced extra pass (0 = skip the pass)")
+    ap.add_argument("--tree", default="", help="override the draft tree as depth,topk,total (default: the config's 6,10,60)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-roofline-pass", action="store_true", help="skip the instrumented passes (for profilers)")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -40,13 +43,32 @@ def parse():
     return ap.parse_args()
 
 
-def run_cycles(eng, n_cycles):
+def run_cycles(eng, n_cycles, out=None):
     emitted = 0
     for _ in range(n_cycles):
         t = eng.draft_tree()
         eng.verify(t)
-        emitted += len(eng.accept(t))
+        toks = eng.accept(t)
+        emitted += len(toks)
+        if out is not None:
+            out.extend(toks)
     return emitted
+
+
+def run_forced_cycles(eng, n_cycles, stream, pos, accept_per_cycle):
+    """Cycles on teacher-forced trees: the known continuation (from plain decoding) is grafted into every drafted tree
+    so that `accept_per_cycle` draft tokens are accepted; returns (tokens emitted, new position, all matched)."""
+    import workload as wl
+    emitted, ok = 0, True
+    for _ in range(n_cycles):
+        t = eng.draft_tree()
+        wl.graft_continuation(t.token, t.parent, t.depth, t.n_nodes, stream[pos:pos + accept_per_cycle])
+        eng.verify(t)
+        toks = eng.accept(t)
+        ok &= toks == stream[pos:pos + len(toks)]
+        pos += len(toks)
+        emitted += len(toks)
+    return emitted, pos, ok
 
 
 def cpu_baseline(sh, layers_timed=2):
@@ -108,11 +130,14 @@ def main():
     sh = wl.BY_NAME[a.config]
     if a.layers:
         sh = sh.with_(n_layers=a.layers, name=f"{sh.name}-{a.layers}layer")
+    if a.tree:
+        d_, k_, n_ = (int(x) for x in a.tree.split(","))
+        sh = sh.with_(tree_depth=d_, tree_topk=k_, tree_total=n_)
     torch.cuda.set_device(0)
     weights = P.pack_weights(wl.iter_device_weights(sh, "cuda"))
     prompt = wl.make_prompt(sh)
     total_cycles = a.warmup + a.steps
-    max_seq = sh.prompt_len + (sh.tree_depth + 1) * total_cycles + sh.tree_total + 32
+    max_seq = sh.prompt_len + (sh.tree_depth + 1) * (total_cycles + 1) + sh.tree_total + 32
 
     # ---- pass A: the timed region ------------------------------------------------------------
     eng = P.Engine(sh, weights, max_seq=max_seq)
@@ -132,14 +157,17 @@ def main():
     ms_per_step = dt / a.steps * 1e3
 
     # plain autoregressive decoding through the same kernels (tree = the root alone): the 1.00x reference
+    forced_accept = max(0, min(sh.tree_depth, a.forced_accept))
+    plain_extra = (total_cycles * (forced_accept + 1) + 1 - total_cycles) if forced_accept else 0
     plain = P.Engine(sh, weights, max_seq=max_seq, tree=(1, 1, 1))
-    plain.prefill(prompt)
-    run_cycles(plain, a.warmup)
+    stream = [plain.prefill(prompt)]
+    run_cycles(plain, a.warmup, stream)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    pe = run_cycles(plain, a.steps)
+    pe = run_cycles(plain, a.steps, stream)
     torch.cuda.synchronize()
     plain_dt = time.perf_counter() - t0
+    run_cycles(plain, plain_extra, stream)                    # untimed: the continuation the forced mode grafts
     plain.close()
 
     by = wl.algorithmic_bytes(sh)
@@ -157,6 +185,25 @@ def main():
         "plain_decode_tokens_per_s": pe / plain_dt,
         "plain_decode_ms_per_token": plain_dt / a.steps * 1e3,
     }
+
+    # ---- teacher-forced trees: the same cycles at a paper-like acceptance length (separately labelled) ----
+    if forced_accept:
+        eng = P.Engine(sh, weights, max_seq=max_seq)
+        first = eng.prefill(prompt)
+        _, pos, ok0 = run_forced_cycles(eng, a.warmup, stream, 1, forced_accept)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        fe, pos, ok1 = run_forced_cycles(eng, a.steps, stream, pos, forced_accept)
+        torch.cuda.synchronize()
+        fdt = time.perf_counter() - t0
+        eng.close()
+        out["teacher_forced"] = {
+            "what": "every drafted tree has the known greedy continuation grafted in on the host (random-init drafts never "
+                    "match the target), so the accept, compaction and hand-off stages run at a paper-like acceptance length; "
+                    "the host-side tree edit is inside the timed loop",
+            "mean_accepted_length": fe / a.steps, "tokens_per_s": fe / fdt, "ms_per_cycle": fdt / a.steps * 1e3,
+            "speedup_over_plain_decode_same_kernels": (fe / fdt) / (pe / plain_dt),
+            "tokens_equal_plain_decoding": bool(first == stream[0] and ok0 and ok1)}
 
     # ---- pass B / C: instrumented with HIP events on the library's stream ---------------------
     if not a.no_roofline_pass:
@@ -182,7 +229,7 @@ def main():
                 achieved = bytes_per_launch / (avg_ms * 1e-3) / 1e9
                 out["roofline"] = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                                    "frac": achieved / HBM_PEAK_GBPS,
-                                   "traffic": MEASURED_TRAFFIC_BYTES_PER_LAUNCH.get(a.config) if not a.layers else None,
+                                   "traffic": MEASURED_TRAFFIC_BYTES_PER_LAUNCH.get(a.config) if not (a.layers or a.tree) else None,
                                    "kernel": "gemm_stream_kernel (verify launches)", "launches_per_step": n_launch,
                                    "avg_launch_ms": avg_ms, "event_interval_ms": raw_ms, "empty_event_pair_ms": pair_ms,
                                    "algorithmic_bytes_per_launch": bytes_per_launch}

@@ -4,6 +4,8 @@ import ctypes as C
 import os
 import re
 
+import numpy as np
+
 import pytest
 
 import workload as wl
@@ -92,3 +94,29 @@ def test_algorithmic_bytes_match_shape_arithmetic():
     assert abs(b["verify_weights"] / 1e9 - 13.21) < 0.01 and b["kv_bytes_per_token"] == 524288
     b = wl.algorithmic_bytes(wl.LLAMA3_70B)
     assert abs(b["verify_weights"] / 1e9 - 139.0) < 0.1 and b["kv_bytes_per_token"] == 327680
+
+
+def test_graft_continuation_keeps_the_tree_valid():
+    """Host-side input preparation used by the benchmark's teacher-forced mode: after grafting, parents still precede
+    children, depths are consistent, and the continuation is a root-to-node path."""
+    import workload as wl
+    rng = np.random.default_rng(0)
+    for trial in range(50):
+        n = int(rng.integers(2, 61))
+        parent = np.full(64, -1, dtype=np.int32)
+        for j in range(1, n):
+            parent[j] = int(rng.integers(0, min(j, 1 + j // 3) if trial % 2 else j))
+        depth = np.zeros(64, dtype=np.int32)
+        for j in range(1, n):
+            depth[j] = depth[parent[j]] + 1
+        token = rng.integers(0, 1000, size=64).astype(np.int32)
+        cont = [int(x) for x in rng.integers(1000, 2000, size=int(rng.integers(0, 7)))]
+        done = wl.graft_continuation(token, parent, depth, n, cont)
+        assert 0 <= done <= len(cont) and parent[0] == -1 and depth[0] == 0
+        cur = 0
+        for d in range(done):
+            kids = [c for c in range(n) if parent[c] == cur and token[c] == cont[d]]
+            assert kids
+            cur = kids[0]
+        for j in range(1, n):
+            assert 0 <= parent[j] < j and depth[j] == depth[parent[j]] + 1

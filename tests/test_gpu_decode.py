@@ -65,6 +65,29 @@ def test_tiny_fp32_spec_matches_oracle_per_cycle(env, tiny_gpu):
         assert np.abs(a["feats"] - b["feats"]).max() < 1e-4
 
 
+@pytest.mark.parametrize("shape", [(1, 1, 2), (2, 3, 5), (15, 1, 16), (3, 16, 40), (6, 10, 60), (15, 16, 128)],
+                         ids=lambda s: "D%d-K%d-N%d" % s)
+def test_tiny_fp32_tree_shapes_match_oracle(env, tiny_gpu, shape):
+    """Other tree shapes, up to the largest the library accepts (depth 15, top-k 16, 128 verified rows: a pool of
+    3600 candidates) and down to a single draft token: tokens, trees and logits against the oracle per cycle."""
+    torch, P = env
+    sh0, hw, w64, prompt, dw = tiny_gpu
+    D, K, N = shape
+    gen = 20
+    sh = sh0.with_(tree_depth=D, tree_topk=K, tree_total=N, gen_tokens=gen)
+    eng = P.Engine(sh, dw)
+    grec, orec = [], []
+    got, gt = eng.generate(prompt, gen, record=grec)
+    want, wt = oracle.spec_decode(w64, sh, prompt, gen, record=orec)
+    assert got == want and gt == wt and len(grec) == len(orec)
+    for a, b in zip(grec, orec):
+        ta, tb = a["tree"], b["tree"]
+        assert ta.n_nodes == tb.n_nodes == N
+        assert list(ta.token) == list(tb.token) and list(ta.parent) == list(tb.parent) and list(ta.depth) == list(tb.depth)
+        assert np.abs(ta.score - tb.score).max() < 5e-5
+        assert np.abs(a["logits"] - b["logits"]).max() < 1e-4
+
+
 def forge_hook(stream, n_prompt, plan, rng, vocab):
     """Graft the known continuation into the GPU-drafted tree (host arrays of the C ABI)."""
     def hook(eng, t):

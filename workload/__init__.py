@@ -175,3 +175,32 @@ def algorithmic_bytes(shape: Shape) -> Dict[str, float]:
         "draft_forward": layer + fc + head,
         "kv_bytes_per_token": kv_per_token,
     }
+
+
+def graft_continuation(token, parent, depth, n_nodes: int, continuation) -> int:
+    """Edits a drafted tree (host arrays: token, parent, depth; node 0 = root, parents precede children) so that it
+    contains `continuation` as a root-to-node path: follows an existing child where there is one, otherwise re-parents
+    a leaf that is not on the path, and overwrites the tokens on the path.  Returns the length of the grafted path.
+    Input preparation only (teacher-forced trees for tests and for the benchmark's acceptance-length mode): it does
+    none of the method's arithmetic."""
+    n = int(n_nodes)
+    par = parent[:n]
+    cur, on_path, done = 0, {0}, 0
+    for tok in continuation:
+        kids = np.nonzero(par == cur)[0]
+        if kids.size:
+            c = int(kids[0])
+        else:
+            n_kids = np.bincount(par[1:], minlength=n)
+            leaves = [int(j) for j in np.nonzero(n_kids == 0)[0] if j > cur and int(j) not in on_path]
+            if not leaves:
+                break
+            c = leaves[0]
+            par[c] = cur
+        token[c] = int(tok)
+        cur = c
+        on_path.add(c)
+        done += 1
+    for j in range(1, n):
+        depth[j] = depth[par[j]] + 1
+    return done
