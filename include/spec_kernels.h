@@ -33,7 +33,9 @@ int spec_k_gemm(int32_t dtype, const void *x, int32_t ldx, int32_t m, int32_t in
  * Sec. 5 related work / Sec. 2 step two).  Row i (of `rows`) has its query in
  * q[i] ([hq*hd], always fp32), sits at key position base + depth[i] and attends to key
  * positions 0 .. base + depth[i]: position p < base is cache row p, position
- * p >= base is cache row base + anc[i*16 + p - base] (anc NULL: row p).
+ * p >= base is cache row base + anc[i*16 + p - base] (anc NULL: row p, a causal
+ * chain).  max_depth = the largest depth[i] (host copy); with anc it must not
+ * exceed 15.  Every cache row a query attends to must hold data.
  * kcache, vcache: [*, hkv*hd].  out: [rows, hq*hd] in dtype.  scratch: fp32,
  * rows*hq*max_parts*(hd+2) floats with max_parts >= (base+max depth)/128 + 2.
  * hd must be 64 or 128, hq/hkv one of 1, 2, 4, 8. */
