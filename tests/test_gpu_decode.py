@@ -190,6 +190,101 @@ def test_tiny_fp32_sampling_accept_matches_oracle_on_forged_peaky_tree(env, tiny
     assert accepted_any
 
 
+def test_call_order_malformed_trees_and_capacity_are_reported(env, tiny_gpu):
+    """Error paths of the C ABI: calls out of order, trees that are not trees, a full cache.  Every failure is an
+    error code with a message; nothing is launched for a rejected call and the context keeps working."""
+    torch, P = env
+    B = P.binding
+    sh, hw, w64, prompt, dw = tiny_gpu
+    eng = P.Engine(sh, dw)
+
+    def code(fn, *a):
+        with pytest.raises(B.SpecError) as e:
+            fn(*a)
+        assert str(e.value)
+        return e.value.code
+
+    t0 = P.Tree.empty(sh.tree_total)
+    assert code(eng.draft_tree) == B.SPEC_ESTATE                  # before prefill
+    assert code(eng.verify, t0) == B.SPEC_ESTATE
+    assert code(eng.accept, t0) == B.SPEC_ESTATE
+    assert code(eng.prefill, []) == B.SPEC_EINVAL
+    assert code(eng.prefill, [sh.vocab]) == B.SPEC_EINVAL         # token out of range
+    first = eng.prefill(prompt)
+    assert code(eng.accept, t0) == B.SPEC_ESTATE                  # nothing verified yet
+    t = eng.draft_tree()
+    good = (t.token.copy(), t.parent.copy(), t.depth.copy(), t.n_nodes)
+
+    def restore():
+        t.token[:], t.parent[:], t.depth[:], t.n_nodes = good[0], good[1], good[2], good[3]
+
+    for edit in ("root", "parent_after", "depth", "token", "count0", "count_big", "too_deep"):
+        restore()
+        if edit == "root": t.token[0] = (first + 1) % sh.vocab
+        if edit == "parent_after": t.parent[2] = 5
+        if edit == "depth": t.depth[3] += 1
+        if edit == "token": t.token[4] = -1
+        if edit == "count0": t.n_nodes = 0
+        if edit == "count_big": t.n_nodes = sh.tree_total + 1
+        if edit == "too_deep":
+            for j in range(1, 16): t.parent[j] = j - 1            # a 15-deep chain is fine ...
+            for j in range(1, 16): t.depth[j] = j
+            t.depth[15] = 16                                      # ... a claimed depth of 16 is not
+        assert code(eng.verify, t) == B.SPEC_EINVAL, edit
+    restore()
+    eng.verify(t)                                                 # the context is still in the DRAFTED state
+    assert code(eng.verify, t) == B.SPEC_ESTATE
+    want = oracle.greedy_decode(w64, sh, prompt, 8)
+    out = [first] + eng.accept(t)
+    assert out == want[:len(out)]
+    eng.close()
+
+    # capacity: room for the prompt, one tree and two more tokens
+    eng = P.Engine(sh, dw, max_seq=len(prompt) + sh.tree_total + 2)
+    toks = [eng.prefill(prompt)]
+    seen = None
+    for _ in range(6):
+        try:                                                      # the draft call already refuses a cycle that cannot fit
+            t = eng.draft_tree()
+            eng.verify(t)
+        except B.SpecError as e:
+            seen = e.code
+            break
+        toks += eng.accept(t)
+    assert seen == B.SPEC_ECAP and toks == want[:len(toks)]
+    eng.close()
+
+
+def test_tiny_fp32_partial_tree_matches_oracle(env, tiny_gpu):
+    """A caller may verify fewer nodes than the configured total (a prefix of the drafted tree is a tree): logits,
+    acceptance and the following cycles agree with the oracle run on the same truncated trees."""
+    torch, P = env
+    sh, hw, w64, prompt, dw = tiny_gpu
+    eng = P.Engine(sh, dw)
+    keep = [7, 1, 16, 3, 11]
+    hook_calls = []
+
+    def gpu_hook(e, t):
+        t.n_nodes = keep[len(hook_calls) % len(keep)]
+        hook_calls.append(t.n_nodes)
+        return t
+
+    ocalls = []
+
+    def oracle_hook(st, t):
+        k = keep[len(ocalls) % len(keep)]
+        ocalls.append(k)
+        return oracle.Tree(t.token[:k].copy(), t.parent[:k].copy(), t.depth[:k].copy(), t.score[:k].copy())
+
+    grec, orec = [], []
+    got, gt = eng.generate(prompt, 24, tree_hook=gpu_hook, record=grec)
+    want, wt = oracle.spec_decode(w64, sh, prompt, 24, tree_hook=oracle_hook, record=orec)
+    assert got == want and gt == wt and hook_calls == ocalls
+    for a, b in zip(grec, orec):
+        assert a["tree"].n_nodes == b["tree"].n_nodes
+        assert np.abs(a["logits"] - b["logits"]).max() < 1e-4
+
+
 BF16_TRUNC = wl.LLAMA2_7B.with_(name="llama2-7b-2layer", n_layers=2, prompt_len=96, gen_tokens=24)
 BF16_GQA = wl.LLAMA3_8B.with_(name="llama3-8b-width-2layer", n_layers=2, vocab=8192, d_ffn=4096, prompt_len=300, gen_tokens=16)
 
