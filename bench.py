@@ -157,7 +157,8 @@ def main():
     ms_per_step = dt / a.steps * 1e3
 
     # plain autoregressive decoding through the same kernels (tree = the root alone): the 1.00x reference
-    forced_accept = max(0, min(sh.tree_depth, a.forced_accept))
+    # (only at T = 0, where the emitted tokens are a function of the weights alone)
+    forced_accept = max(0, min(sh.tree_depth, a.forced_accept)) if sh.temperature == 0 and sh.tree_total > 1 else 0
     plain_extra = (total_cycles * (forced_accept + 1) + 1 - total_cycles) if forced_accept else 0
     plain = P.Engine(sh, weights, max_seq=max_seq, tree=(1, 1, 1))
     stream = [plain.prefill(prompt)]
@@ -179,7 +180,7 @@ def main():
         "warmup": a.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": sh.dtype, "data": "synthetic",
         "config": {"workload": f"{sh.name} shape, random init N(0,0.02), prompt {sh.prompt_len} uniform tokens, "
-                               f"tree depth {sh.tree_depth} top-k {sh.tree_topk} total {sh.tree_total}, T=0, batch 1"},
+                               f"tree depth {sh.tree_depth} top-k {sh.tree_topk} total {sh.tree_total}, T={sh.temperature:g}, batch 1"},
         "ms_per_cycle": ms_per_step,
         "mean_accepted_length": emitted / a.steps,
         "plain_decode_tokens_per_s": pe / plain_dt,

@@ -198,7 +198,7 @@ size_t layout(const spec_config &c, spec_ctx *x, char *base) {
   TAKE(logits, float *, (size_t)std::max(c.tree_total, 1) * v * 4)
   TAKE(dlogits, float *, (size_t)kMaxTopK * v * 4)
   TAKE(rope, float2 *, (size_t)m_max * (c.head_dim / 2) * 8)
-  TAKE(stats, float2 *, (size_t)kMaxNodes * 8)
+  TAKE(stats, float2 *, (size_t)kMaxNodes * argmax_slices(c.vocab) * 8)
   const int n_slices = (v + kTopkSlice - 1) / kTopkSlice;
   TAKE(sc_stat, float2 *, (size_t)kMaxTopK * n_slices * 8)
   TAKE(sc_val, float *, (size_t)kMaxTopK * n_slices * kMaxTopK * 4)

@@ -89,8 +89,9 @@ hipError_t launch_attention(int dtype, const AttnArgs &a, int max_pos, hipStream
 int argmax_slices(int vocab);
 hipError_t launch_rows_argmax(const float *logits, int rows, int vocab, float *part_val, int *part_idx, int *out,
                               hipStream_t st);
-// per row, with x = logit / temp: stats[row] = {max x, sum exp(x - max x)}
-hipError_t launch_rows_softmax_stats(const float *logits, int rows, int vocab, float temp, float2 *stats, hipStream_t st);
+// with x = logit / temp: part[row][slice] = {max x, sum exp(x - max x)} over slices of kTopkSlice entries
+// (argmax_slices(vocab) slices per row); the sampling acceptance merges the slices of the rows it visits.
+hipError_t launch_rows_softmax_stats(const float *logits, int rows, int vocab, float temp, float2 *part, hipStream_t st);
 // per row: top-k (token, log-softmax) pairs, best first, lower token on ties.  Two stages through scratch.
 hipError_t launch_rows_topk_logprob(const float *logits, int rows, int vocab, int k, float *sc_val, int *sc_idx,
                                     float2 *sc_stat, int *top_tok, float *top_lp, hipStream_t st);
@@ -127,7 +128,7 @@ struct AcceptResult {                   // lives on the device; copied to the ho
 };
 hipError_t launch_accept_greedy(const float *amax_val, const int *amax_idx, int n_slices, const int *tree_tok,
                                 const int *tree_par, int n_nodes, AcceptResult *res, hipStream_t st);
-hipError_t launch_accept_sample(const float *logits, int vocab, const float2 *stats, float temp, const int *tree_tok,
+hipError_t launch_accept_sample(const float *logits, int vocab, const float2 *stat_part, float temp, const int *tree_tok,
                                 const int *tree_par, int n_nodes, uint64_t seed, uint32_t cycle, AcceptResult *res,
                                 hipStream_t st);
 // Sample one token from softmax(logits / temp) by Gumbel-max with stream (seed, cycle, node).

@@ -88,22 +88,48 @@ hipError_t launch_rows_argmax(const float *logits, int rows, int vocab, float *p
   return hipGetLastError();
 }
 
-// ---- per-row softmax statistics at temperature T: max(x) and sum exp(x - max), x = logit / T
-__global__ __launch_bounds__(kSelThreads) void rows_softmax_stats_kernel(const float *logits, int vocab, float temp,
-                                                                         float2 *stats) {
+// ---- per-row softmax statistics at temperature T, x = logit / T ----------------------------
+// One workgroup per (slice of kTopkSlice entries, row): part[row][slice] = {max x, sum exp(x - max x)} over the
+// slice.  merge_softmax_stats (one wavefront) turns a row's slices into {max x, sum exp(x - max x)} of the row.
+__global__ __launch_bounds__(kSelThreads) void softmax_slice_kernel(const float *logits, int vocab, float temp, int n_slices,
+                                                                    float2 *part) {
+  constexpr int PER = kTopkSlice / kSelThreads;   // 16
   __shared__ float sh[16];
-  const float *row = logits + (size_t)blockIdx.x * vocab;
-  float m = -INFINITY;
-  for (int c = threadIdx.x; c < vocab; c += kSelThreads) m = fmaxf(m, row[c] / temp);
+  const int slice = blockIdx.x, rowi = blockIdx.y, t = threadIdx.x;
+  const int c0 = slice * kTopkSlice;
+  const float *row = logits + (size_t)rowi * vocab;
+  float v[PER];
+#pragma unroll
+  for (int e = 0; e < PER; e++) {
+    const int c = c0 + t + e * kSelThreads;
+    v[e] = c < vocab ? row[c] / temp : -INFINITY;
+  }
+  float m = v[0];
+#pragma unroll
+  for (int e = 1; e < PER; e++) m = fmaxf(m, v[e]);
   m = block_max(m, sh);
   float s = 0.f;
-  for (int c = threadIdx.x; c < vocab; c += kSelThreads) s += expf(row[c] / temp - m);
+#pragma unroll
+  for (int e = 0; e < PER; e++) s += expf(v[e] - m);        // exp(-inf) = 0 for padding
   s = block_sum(s, sh);
-  if (threadIdx.x == 0) stats[blockIdx.x] = make_float2(m, s);
+  if (t == 0) part[(size_t)rowi * n_slices + slice] = make_float2(m, s);
 }
-hipError_t launch_rows_softmax_stats(const float *logits, int rows, int vocab, float temp, float2 *stats, hipStream_t st) {
+__device__ __forceinline__ float2 merge_softmax_stats(const float2 *part, int n_slices, int row, int lane) {
+  const float2 *stat = part + (size_t)row * n_slices;
+  float m = -INFINITY;
+  for (int sl = lane; sl < n_slices; sl += 64) m = fmaxf(m, stat[sl].x);
+  m = wave_max(m);
+  float tot = 0.f;
+  for (int s0 = 0; s0 < n_slices; s0 += 64) {              // slices in ascending groups of 64, fixed butterfly inside
+    const int sl = s0 + lane;
+    tot += wave_sum(sl < n_slices ? stat[sl].y * expf(stat[sl].x - m) : 0.f);
+  }
+  return make_float2(m, tot);
+}
+hipError_t launch_rows_softmax_stats(const float *logits, int rows, int vocab, float temp, float2 *part, hipStream_t st) {
   if (rows < 1 || vocab < 1 || !(temp > 0.f)) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(rows_softmax_stats_kernel, dim3(rows), dim3(kSelThreads), 0, st, logits, vocab, temp, stats);
+  const int n_slices = argmax_slices(vocab);
+  hipLaunchKernelGGL(softmax_slice_kernel, dim3(n_slices, rows), dim3(kSelThreads), 0, st, logits, vocab, temp, n_slices, part);
   return hipGetLastError();
 }
 
@@ -389,32 +415,54 @@ __device__ __forceinline__ int gumbel_argmax(const float *row, int vocab, float 
 // deterministically by the draft (top-k), so each is a point-mass proposal: child c is accepted
 // with probability p'(c), where p' is the target distribution with the already rejected siblings
 // removed and renormalised; when all children are rejected the bonus token is drawn from p'.
-__global__ __launch_bounds__(kSelThreads) void accept_sample_kernel(const float *logits, int vocab, const float2 *stats,
-                                                                    float temp, const int *tree_tok, const int *tree_par,
-                                                                    int n_nodes, uint64_t seed, uint32_t cycle,
-                                                                    AcceptResult *res) {
+// One workgroup.  Per visited node: the first wavefront merges the row's softmax slices and lists the
+// node's children, all threads fetch the children's logits together, thread 0 runs the (inherently
+// sequential) accept/reject chain on those values, and the bonus draw uses the whole workgroup.
+constexpr int kAcceptThreads = 1024;
+__global__ __launch_bounds__(kAcceptThreads) void accept_sample_kernel(const float *logits, int vocab, const float2 *stat_part,
+                                                                       int n_slices, float temp, const int *tree_tok,
+                                                                       const int *tree_par, int n_nodes, uint64_t seed,
+                                                                       uint32_t cycle, AcceptResult *res) {
   __shared__ float shv[16];
   __shared__ int shi[16];
   __shared__ int rem[kMaxNodes];
-  __shared__ int sh_next, sh_nrem;
+  __shared__ int kid[kMaxNodes];
+  __shared__ float kid_x[kMaxNodes];
+  __shared__ int sh_next, sh_nrem, sh_nkid;
+  __shared__ float2 sh_stat;
+  const int t = threadIdx.x;
   int cur = 0, m = 0;
-  if (threadIdx.x == 0) res->node[0] = 0;
+  if (t == 0) res->node[0] = 0;
   for (int step = 0; step <= kMaxDepth; step++) {
     const uint64_t stream = rng_stream(seed, cycle, (uint32_t)cur);
-    if (threadIdx.x == 0) {
-      const float *row = logits + (size_t)cur * vocab;
-      const float2 st = stats[cur];
+    const float *row = logits + (size_t)cur * vocab;
+    if (t < 64) {
+      const float2 st = merge_softmax_stats(stat_part, n_slices, cur, t);
+      if (t == 0) {
+        sh_stat = st;
+        int nk = 0;
+        if (m < kMaxDepth)
+          for (int c = cur + 1; c < n_nodes; c++)
+            if (tree_par[c] == cur) kid[nk++] = c;            // node order = descending draft probability
+        sh_nkid = nk;
+      }
+    }
+    __syncthreads();
+    const int n_kid = sh_nkid;
+    if (t < n_kid) kid_x[t] = row[tree_tok[kid[t]]];
+    __syncthreads();
+    if (t == 0) {
+      const float2 st = sh_stat;
       float removed = 0.f;                                  // probability mass of the rejected siblings
-      int n_rem = 0, next = -1, ord = 0;
-      for (int c = cur + 1; c < n_nodes && next < 0 && m < kMaxDepth; c++) {
-        if (tree_par[c] != cur) continue;
+      int n_rem = 0, next = -1;
+      for (int ord = 0; ord < n_kid && next < 0; ord++) {
+        const int c = kid[ord];
         const int tok = tree_tok[c];
         bool dup = false;
         for (int r = 0; r < n_rem; r++) dup |= rem[r] == tok;
-        const float p0 = dup ? 0.f : expf(row[tok] / temp - st.x) / st.y;
+        const float p0 = dup ? 0.f : expf(kid_x[ord] / temp - st.x) / st.y;
         const float rest = 1.0f - removed;
         const float u = rng_uniform(stream, (uint64_t)ord);
-        ord++;
         if (u < p0 / rest) { next = c; break; }
         if (!dup) { removed += p0; rem[n_rem++] = tok; }
         if (!(1.0f - removed > 0.f)) { next = c; break; }   // nothing left in the residual: c was certain
@@ -424,28 +472,28 @@ __global__ __launch_bounds__(kSelThreads) void accept_sample_kernel(const float 
     __syncthreads();
     const int next = sh_next, n_rem = sh_nrem;
     if (next >= 0) {
-      if (threadIdx.x == 0) { res->token[m] = tree_tok[next]; res->node[m + 1] = next; }
+      if (t == 0) { res->token[m] = tree_tok[next]; res->node[m + 1] = next; }
       cur = next; m++;
       __syncthreads();
       continue;
     }
-    const int bonus = gumbel_argmax(logits + (size_t)cur * vocab, vocab, temp, stream, rem, n_rem, shv, shi);
-    if (threadIdx.x == 0) res->token[m] = bonus;
+    const int bonus = gumbel_argmax(row, vocab, temp, stream, rem, n_rem, shv, shi);
+    if (t == 0) res->token[m] = bonus;
     break;
   }
-  if (threadIdx.x == 0) res->n_acc = m;
+  if (t == 0) res->n_acc = m;
 }
-hipError_t launch_accept_sample(const float *logits, int vocab, const float2 *stats, float temp, const int *tree_tok,
+hipError_t launch_accept_sample(const float *logits, int vocab, const float2 *stat_part, float temp, const int *tree_tok,
                                 const int *tree_par, int n_nodes, uint64_t seed, uint32_t cycle, AcceptResult *res,
                                 hipStream_t st) {
   if (n_nodes < 1 || n_nodes > kMaxNodes || !(temp > 0.f)) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(accept_sample_kernel, dim3(1), dim3(kSelThreads), 0, st, logits, vocab, stats, temp, tree_tok, tree_par,
-                     n_nodes, seed, cycle, res);
+  hipLaunchKernelGGL(accept_sample_kernel, dim3(1), dim3(kAcceptThreads), 0, st, logits, vocab, stat_part, argmax_slices(vocab),
+                     temp, tree_tok, tree_par, n_nodes, seed, cycle, res);
   return hipGetLastError();
 }
 
-__global__ __launch_bounds__(kSelThreads) void sample_row_kernel(const float *logits, int vocab, float temp, uint64_t seed,
-                                                                 uint32_t cycle, uint32_t node, int *out) {
+__global__ __launch_bounds__(kAcceptThreads) void sample_row_kernel(const float *logits, int vocab, float temp, uint64_t seed,
+                                                                    uint32_t cycle, uint32_t node, int *out) {
   __shared__ float shv[16];
   __shared__ int shi[16];
   const int tok = gumbel_argmax(logits, vocab, temp, rng_stream(seed, cycle, node), nullptr, 0, shv, shi);
@@ -454,7 +502,7 @@ __global__ __launch_bounds__(kSelThreads) void sample_row_kernel(const float *lo
 hipError_t launch_sample_row(const float *logits, int vocab, float temp, uint64_t seed, uint32_t cycle, uint32_t node,
                              int *out, hipStream_t st) {
   if (vocab < 1 || !(temp > 0.f)) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(sample_row_kernel, dim3(1), dim3(kSelThreads), 0, st, logits, vocab, temp, seed, cycle, node, out);
+  hipLaunchKernelGGL(sample_row_kernel, dim3(1), dim3(kAcceptThreads), 0, st, logits, vocab, temp, seed, cycle, node, out);
   return hipGetLastError();
 }
 
