@@ -363,6 +363,30 @@ def test_bf16_spec_equals_greedy_bit_exact(env, bf16_model):
         assert np.array_equal(r["logits"][0], plain_at[r["n"]])
 
 
+@pytest.mark.parametrize("shape", [(15, 16, 128), (8, 10, 80), (2, 4, 7)], ids=lambda s: "D%d-K%d-N%d" % s)
+def test_bf16_other_tree_shapes_equal_greedy_bit_exact(env, bf16_model, shape):
+    """The bit-exactness argument does not depend on the tree shape: trees of 80 and 128 rows (three and four
+    32-row token tiles in the GEMM, more query blocks in the attention) and a tiny one, forged to accept up to
+    the tree's depth, emit the plain-decoding stream and the same root-row logits."""
+    torch, P = env
+    sh0, hw, dw, prompt = bf16_model
+    D, K, N = shape
+    sh = sh0.with_(tree_depth=D, tree_topk=K, tree_total=N)
+    gen = 20
+    cap = len(prompt) + gen + D + N + 40
+    plain = P.Engine(sh, dw, tree=(1, 1, 1), max_seq=cap)
+    prec = []
+    greedy, _ = plain.generate(prompt, gen + D + 2, record=prec)
+    rng = np.random.default_rng(1)
+    spec = P.Engine(sh, dw, max_seq=cap)
+    srec = []
+    got, taus = spec.generate(prompt, gen, tree_hook=forge_hook(greedy, len(prompt), lambda n: n % (min(D, 6) + 1), rng, sh.vocab), record=srec)
+    assert got == greedy[:gen] and max(taus) >= min(D, 3)
+    plain_at = {r["n"]: r["logits"][0] for r in prec}
+    for r in srec:
+        assert np.array_equal(r["logits"][0], plain_at[r["n"]])
+
+
 def test_graph_replay_equals_eager_launches(env, bf16_model):
     """The verify forward replayed from a HIP graph gives the same bits as individually launched kernels,
     on every cycle, with eager work (draft, accept, host syncs) between the replays."""
