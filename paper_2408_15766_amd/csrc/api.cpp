@@ -20,7 +20,7 @@ namespace {
 
 enum State { CREATED = 0, READY = 1, DRAFTED = 2, VERIFIED = 3 };
 
-constexpr int kPrefillChunk = 64;     // prompt rows per target forward during prefill
+constexpr int kPrefillChunk = 128;     // prompt rows per target forward during prefill
 constexpr int kMaxGemmEvents = 2048;  // event pairs kept per cycle at profile level 2
 
 struct GemmPlan { int n_split; };
