@@ -22,8 +22,9 @@ extern "C" {
  * x[i][k] * w[c][k].  Up to three weight matrices (w0, w1, w2; rows0..2 rows
  * each, [rows, in] in the PACKED layout of spec_pack_weight; unused ones
  * NULL / 0) share x and write consecutive column ranges.  x: [m, in] with row stride ldx elements,
- * 1 <= m <= 128.  part: fp32 [n_split][m_pad][ldp], ldp >= rows0+rows1+rows2,
- * m_pad >= m.  The K ranges are whole slabs (256 bf16 / 128 fp32 elements),
+ * 1 <= m <= 4096 (more than 128 rows run as tiles of 128 that share the weight
+ * rows through L2: the prefill case).  part: fp32 [n_split][m_pad][ldp],
+ * ldp >= rows0+rows1+rows2, m_pad >= m.  The K ranges are whole slabs (256 bf16 / 128 fp32 elements),
  * balanced to within one slab; the caller sums the splits in ascending order. */
 int spec_k_gemm(int32_t dtype, const void *x, int32_t ldx, int32_t m, int32_t in,
                 const void *w0, int32_t rows0, const void *w1, int32_t rows1, const void *w2, int32_t rows2,

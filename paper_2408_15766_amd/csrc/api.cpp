@@ -20,7 +20,7 @@ namespace {
 
 enum State { CREATED = 0, READY = 1, DRAFTED = 2, VERIFIED = 3 };
 
-constexpr int kPrefillChunk = 128;     // prompt rows per target forward during prefill
+constexpr int kPrefillChunk = 512;     // prompt rows per target forward during prefill
 constexpr int kMaxGemmEvents = 2048;  // event pairs kept per cycle at profile level 2
 
 struct GemmPlan { int n_split; };
@@ -824,7 +824,7 @@ int spec_k_gemm(int32_t dtype, const void *x, int32_t ldx, int32_t m, int32_t in
                 int32_t n_split, void *stream) {
   if (!x || !w0 || !part || rows0 < 1 || (dtype != 0 && dtype != 1)) return SPEC_EINVAL;
   const int epl = dtype == 1 ? 8 : 4;
-  if (in < 1 || in % epl || ldx % epl || m < 1 || m > 128 || m_pad < m) return SPEC_EINVAL;
+  if (in < 1 || in % epl || ldx % epl || m < 1 || m > 4096 || m_pad < m) return SPEC_EINVAL;
   const void *ws[3] = {w0, w1, w2};
   const int rs[3] = {rows0, w1 ? rows1 : 0, (w1 && w2) ? rows2 : 0};
   GemmArgs a{};

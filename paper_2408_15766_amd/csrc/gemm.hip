@@ -1,7 +1,7 @@
 // Weight-streaming skinny GEMM for gfx950:  P[s][i][col] = sum_{k in split s} X[i][k] * W[col][k]
 //
 // Every projection of the decode path (QKV, O, gate/up, down, draft fc, LM head)
-// multiplies a handful of token rows (M <= 128: the verified tree, the draft
+// multiplies a handful of token rows (M <= 128 per tile: the verified tree, the draft
 // frontier, or one row in plain decoding) by a weight matrix that is read once.
 // The step is bound by HBM bandwidth (about 2*M flop per weight byte pair), so
 // the design goal is to keep many 16-byte weight loads in flight per lane and
@@ -103,11 +103,24 @@ __global__ __launch_bounds__(kGemmThreads, (TB <= 2 && kStages <= 3) ? 2 : 1) vo
   // A wave past the last block recomputes the last block and stores nothing, so that every wave
   // runs the same branch-free loop and the same barriers.
   // SwiGLU mode pairs blocks instead: waves 0,1 take gate blocks 2x, 2x+1 and waves 2,3 the same up blocks.
+  // Workgroup coordinates: (bx = row group, by = K split, mt = 128-row tile of X).  With several tiles the
+  // launch is one-dimensional and the tiles of one (row group, split) take ids 8 apart inside a window of
+  // 8 * m_tiles consecutive ids: they run at the same time on the same XCD, so the weight rows they share
+  // come from HBM once and from that XCD's L2 afterwards.
+  int bx = blockIdx.x, by = blockIdx.y, mt = 0;
+  if (a.m_tiles > 1) {
+    const int per = 8 * a.m_tiles;
+    const int q = ((int)blockIdx.x / per) * 8 + ((int)blockIdx.x % 8);
+    mt = ((int)blockIdx.x % per) / 8;
+    if (q >= a.grid_x * a.n_split) return;                     // padding of the id space; whole workgroup
+    bx = q % a.grid_x; by = q / a.grid_x;
+  }
+  const int m_loc = min(a.m - mt * 128, 128);                  // token rows of this tile
   const bool swiglu = a.act != nullptr;
   const int e0 = a.seg_blocks[0], e1 = e0 + (a.nseg > 1 ? a.seg_blocks[1] : 0);
   const int half_waves = kGemmWaves / 2;
-  const int pair_raw = blockIdx.x * half_waves + (wave % half_waves);
-  const int blk_raw = swiglu ? (pair_raw < e0 ? (wave / half_waves) * e0 + pair_raw : a.total_blocks) : blockIdx.x * kGemmWaves + wave;
+  const int pair_raw = bx * half_waves + (wave % half_waves);
+  const int blk_raw = swiglu ? (pair_raw < e0 ? (wave / half_waves) * e0 + pair_raw : a.total_blocks) : bx * kGemmWaves + wave;
   const bool active = blk_raw < a.total_blocks;
   const int blk = active ? blk_raw : a.total_blocks - 1;
   const int seg = blk < e0 ? 0 : (blk < e1 ? 1 : 2);
@@ -121,8 +134,8 @@ __global__ __launch_bounds__(kGemmThreads, (TB <= 2 && kStages <= 3) ? 2 : 1) vo
   constexpr int KSLAB = kSlabRowBytes / (int)sizeof(T);
   const int n_it_total = (a.in + KI - 1) / KI;                         // tiles along k (K zero-padded to KI)
   const int n_slabs_total = (n_it_total + kSlabIters - 1) / kSlabIters;
-  const int it_begin = (int)((long long)blockIdx.y * n_slabs_total / a.n_split) * kSlabIters;
-  const int it_end = min(n_it_total, (int)((long long)(blockIdx.y + 1) * n_slabs_total / a.n_split) * kSlabIters);
+  const int it_begin = (int)((long long)by * n_slabs_total / a.n_split) * kSlabIters;
+  const int it_end = min(n_it_total, (int)((long long)(by + 1) * n_slabs_total / a.n_split) * kSlabIters);
   const int k_begin = it_begin * KI;
   const int n_iter = it_end - it_begin;
   const int n_slab = (n_iter + kSlabIters - 1) / kSlabIters;
@@ -147,7 +160,7 @@ __global__ __launch_bounds__(kGemmThreads, (TB <= 2 && kStages <= 3) ? 2 : 1) vo
 #pragma unroll
     for (int j = 0; j < 8; j++) dst[j] = __builtin_nontemporal_load((const u32x4_t *)(p + j * 1024));   // read once: do not keep in cache
   };
-  const char *xbase = (const char *)a.x;
+  const char *xbase = (const char *)a.x + (size_t)mt * 128 * a.ldx * sizeof(T);
   auto load_x = [&](int slab) {
     const int k0 = k_begin + slab * kSlabIters * KI;
 #pragma unroll
@@ -155,7 +168,7 @@ __global__ __launch_bounds__(kGemmThreads, (TB <= 2 && kStages <= 3) ? 2 : 1) vo
       const int q = tid + i * kGemmThreads;
       const int r = q / (kSlabRowBytes / 16), cc = q % (kSlabRowBytes / 16);
       const int kk = k0 + cc * EPL;
-      xr[i] = *(const u32x4_t *)(xbase + ((size_t)(r < a.m ? r : 0) * a.ldx + (kk < a.in ? kk : 0)) * sizeof(T));
+      xr[i] = *(const u32x4_t *)(xbase + ((size_t)(r < m_loc ? r : 0) * a.ldx + (kk < a.in ? kk : 0)) * sizeof(T));
     }
   };
   auto store_x = [&](int buf) {
@@ -235,25 +248,25 @@ __global__ __launch_bounds__(kGemmThreads, (TB <= 2 && kStages <= 3) ? 2 : 1) vo
     __syncthreads();
     if (wave >= half_waves || !active || row >= seg_rows) return;
     const float *src = xch + ((size_t)wave * 64 + lane) * (TB * 16);
-    T *act = (T *)a.act + row;
+    T *act = (T *)a.act + (size_t)mt * 128 * seg_rows + row;
 #pragma unroll
     for (int t = 0; t < TB; t++)
 #pragma unroll
       for (int v = 0; v < 16; v++) {
         const int i = t * 32 + 8 * (v >> 2) + 4 * g + (v & 3);
         const float gv = acc[t][v], uv = src[t * 16 + v];
-        if (i < a.m) act[(size_t)i * seg_rows] = from_f32<T>(gv / (1.0f + expf(-gv)) * uv);
+        if (i < m_loc) act[(size_t)i * seg_rows] = from_f32<T>(gv / (1.0f + expf(-gv)) * uv);
       }
     return;
   }
   if (!active || row >= seg_rows) return;
-  float *out = a.part + ((size_t)blockIdx.y * a.m_pad) * a.ldp + seg_col0 + row;
+  float *out = a.part + ((size_t)by * a.m_pad + (size_t)mt * 128) * a.ldp + seg_col0 + row;
 #pragma unroll
   for (int t = 0; t < TB; t++)
 #pragma unroll
     for (int v = 0; v < 16; v++) {
       const int i = t * 32 + 8 * (v >> 2) + 4 * g + (v & 3);
-      if (i < a.m) out[(size_t)i * a.ldp] = acc[t][v];
+      if (i < m_loc) out[(size_t)i * a.ldp] = acc[t][v];
     }
 }
 
@@ -318,13 +331,16 @@ hipError_t gemm_init() {
 }
 
 template <typename T>
-static hipError_t launch_t(const GemmArgs &a, hipStream_t st) {
-  const int tb = (a.m + 31) / 32;
-  dim3 grid((a.total_blocks + kGemmWaves - 1) / kGemmWaves, a.n_split);
+static hipError_t launch_t(GemmArgs a, hipStream_t st) {
+  a.m_tiles = (a.m + 127) / 128;
+  const int tb = a.m_tiles > 1 ? 4 : (a.m + 31) / 32;
+  a.grid_x = (a.total_blocks + kGemmWaves - 1) / kGemmWaves;
   if (a.act != nullptr) {                                      // SwiGLU mode: one workgroup per two gate/up block pairs
     if (a.nseg != 2 || a.n_split != 1 || a.seg_rows[0] != a.seg_rows[1] || (kGemmWaves & 1)) return hipErrorInvalidValue;
-    grid = dim3((a.seg_blocks[0] + kGemmWaves / 2 - 1) / (kGemmWaves / 2), 1);
+    a.grid_x = (a.seg_blocks[0] + kGemmWaves / 2 - 1) / (kGemmWaves / 2);
   }
+  dim3 grid(a.grid_x, a.n_split);
+  if (a.m_tiles > 1) grid = dim3((a.grid_x * a.n_split + 7) / 8 * 8 * a.m_tiles, 1);   // see the kernel's id decoding
   const size_t lds = (size_t)2 * tb * 32 * kSlabStride;
   if (lds > 160 * 1024) return hipErrorInvalidValue;
   switch (tb) {
@@ -343,7 +359,7 @@ int gemm_rows_per_group() { return 32 * kGemmWaves; }
 
 hipError_t launch_gemm(int dtype, const GemmArgs &a, hipStream_t st) {
   { hipError_t e = gemm_init(); if (e != hipSuccess) return e; }
-  if (a.m < 1 || a.m > 128 || a.nseg < 1 || a.nseg > 3 || a.n_split < 1 || a.in < 1) return hipErrorInvalidValue;
+  if (a.m < 1 || a.m_pad < a.m || a.nseg < 1 || a.nseg > 3 || a.n_split < 1 || a.in < 1) return hipErrorInvalidValue;
   if (a.n_split > (a.in + gemm_k_per_slab(dtype) - 1) / gemm_k_per_slab(dtype)) return hipErrorInvalidValue;   // no empty split
   return dtype == 1 ? launch_t<bf16_t>(a, st) : launch_t<float>(a, st);
 }

@@ -15,7 +15,7 @@ constexpr int kTopkSlice = 4096;       // vocabulary entries per first-stage top
 
 // ---- gemm.hip --------------------------------------------------------------------------------
 struct GemmArgs {
-  const void *x;  int ldx;  int m;      // X [m, in], row stride ldx elements, 1 <= m <= 128
+  const void *x;  int ldx;  int m;      // X [m, in], row stride ldx elements; m > 128 runs as tiles of 128 rows (prefill)
   int in;                               // K, a multiple of 16 bytes / element size
   const void *seg_w[3];                 // up to three PACKED weight matrices ([rows, in] before packing) sharing X (e.g. q, k, v)
   int seg_rows[3];
@@ -28,6 +28,7 @@ struct GemmArgs {
   // A workgroup then owns two gate blocks and the SAME two up blocks and writes
   // act[i][c] = silu(gate) * up in the storage type instead of partial sums.
   void *act;
+  int m_tiles, grid_x;                  // set by launch_gemm: 128-row tiles of X, workgroups per tile and split
 };
 hipError_t launch_gemm(int dtype, const GemmArgs &a, hipStream_t st);
 hipError_t gemm_init();                 // one-time kernel attributes; call outside any stream capture

@@ -40,6 +40,9 @@ GEMM_CASES = [
     ("bf16", 64, 1280, (100,), 1),              # ragged rows, odd slab count
     ("bf16", 60, 256, (1000,), 1),              # one slab only
     ("bf16", 100, 2048, (160,), 2),             # four token blocks (tree-shape sweep sizes)
+    ("bf16", 200, 1024, (96, 40), 2),           # two 128-row tiles (prefill), ragged second tile, two segments
+    ("bf16", 512, 768, (300,), 1),              # four full tiles, ragged rows
+    ("fp32", 129, 256, (64,), 1),               # second tile of a single row
 ]
 
 
