@@ -103,19 +103,8 @@ __global__ __launch_bounds__(kGemmThreads, (TB <= 2 && kStages <= 3) ? 2 : 1) vo
   // A wave past the last block recomputes the last block and stores nothing, so that every wave
   // runs the same branch-free loop and the same barriers.
   // SwiGLU mode pairs blocks instead: waves 0,1 take gate blocks 2x, 2x+1 and waves 2,3 the same up blocks.
-  // Workgroup coordinates: (bx = row group, by = K split, mt = 128-row tile of X).  With several tiles the
-  // launch is one-dimensional and the tiles of one (row group, split) take ids 8 apart inside a window of
-  // 8 * m_tiles consecutive ids: they run at the same time on the same XCD, so the weight rows they share
-  // come from HBM once and from that XCD's L2 afterwards.
-  int bx = blockIdx.x, by = blockIdx.y, mt = 0;
-  if (a.m_tiles > 1) {
-    const int per = 8 * a.m_tiles;
-    const int q = ((int)blockIdx.x / per) * 8 + ((int)blockIdx.x % 8);
-    mt = ((int)blockIdx.x % per) / 8;
-    if (q >= a.grid_x * a.n_split) return;                     // padding of the id space; whole workgroup
-    bx = q % a.grid_x; by = q / a.grid_x;
-  }
-  const int m_loc = min(a.m - mt * 128, 128);                  // token rows of this tile
+  const int bx = blockIdx.x, by = blockIdx.y, mt = 0;
+  const int m_loc = a.m;                                       // (more than 128 rows go to gemm_tiled_kernel)
   const bool swiglu = a.act != nullptr;
   const int e0 = a.seg_blocks[0], e1 = e0 + (a.nseg > 1 ? a.seg_blocks[1] : 0);
   const int half_waves = kGemmWaves / 2;
@@ -270,6 +259,169 @@ __global__ __launch_bounds__(kGemmThreads, (TB <= 2 && kStages <= 3) ? 2 : 1) vo
     }
 }
 
+// ---- more than 128 token rows (prefill) -------------------------------------------------------
+// The same contraction when X has several 128-row tiles.  One launch covers all tiles; a workgroup owns
+// (256 weight rows, one K split, one tile).  Here the matrix cores are the limit, and with one weight block
+// per wave every MFMA would need its own token fragment from LDS (LDS bandwidth runs out first), so a wave
+// streams TWO weight blocks and uses each fragment twice.  In SwiGLU mode the two blocks are the gate and
+// the up block of the same columns, so the activation is formed in registers.  Tiles of the same weight rows
+// take workgroup ids 8 apart inside a window of 8 * m_tiles ids: they run together on one XCD and share the
+// weights through its L2 (default cache policy instead of the read-once hint).
+template <typename T>
+__global__ __launch_bounds__(kGemmThreads, 1) void gemm_tiled_kernel(GemmArgs a) {
+  constexpr int TB = 4, WB = 2;
+  constexpr int EPL = GemmTraits<T>::kEpl;
+  constexpr int KI = 2 * kLaneBytes / (int)sizeof(T);
+  constexpr int XCH = TB * 32 * (kSlabRowBytes / 16) / kGemmThreads;
+  extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+  constexpr int kSlabBytes = TB * 32 * kSlabStride;
+  static_assert(kSlabIters == 2, "the two ring stages alternate with the two iterations of a slab");
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int c = lane & 31, g = lane >> 5;
+  const int per = 8 * a.m_tiles;
+  const int q = ((int)blockIdx.x / per) * 8 + ((int)blockIdx.x % 8);
+  const int mt = ((int)blockIdx.x % per) / 8;
+  if (q >= a.grid_x * a.n_split) return;                       // padding of the id space; whole workgroup
+  const int bx = q % a.grid_x, by = q / a.grid_x;
+  const int m_loc = min(a.m - mt * 128, 128);
+
+  const bool swiglu = a.act != nullptr;
+  const int e0 = a.seg_blocks[0], e1 = e0 + (a.nseg > 1 ? a.seg_blocks[1] : 0);
+  const int unit = bx * kGemmWaves + wave;                     // pair of blocks (SwiGLU: gate/up pair of the same columns)
+  bool active[WB]; int seg_rows[WB], seg_col0[WB], row[WB];
+  const char *wstream[WB];
+  constexpr int KSLAB = kSlabRowBytes / (int)sizeof(T);
+  const int n_it_total = (a.in + KI - 1) / KI;
+  const int n_slabs_total = (n_it_total + kSlabIters - 1) / kSlabIters;
+  const int it_begin = (int)((long long)by * n_slabs_total / a.n_split) * kSlabIters;
+  const int it_end = min(n_it_total, (int)((long long)(by + 1) * n_slabs_total / a.n_split) * kSlabIters);
+  const int k_begin = it_begin * KI;
+  const int n_iter = it_end - it_begin;
+  const int n_slab = (n_iter + kSlabIters - 1) / kSlabIters;
+#pragma unroll
+  for (int wb = 0; wb < WB; wb++) {
+    const int blk_raw = swiglu ? (unit < e0 ? wb * e0 + unit : a.total_blocks) : unit * WB + wb;
+    active[wb] = blk_raw < a.total_blocks;
+    const int blk = active[wb] ? blk_raw : a.total_blocks - 1;
+    const int seg = blk < e0 ? 0 : (blk < e1 ? 1 : 2);
+    const int b0 = seg == 0 ? 0 : (seg == 1 ? e0 : e1);
+    seg_rows[wb] = seg == 0 ? a.seg_rows[0] : (seg == 1 ? a.seg_rows[1] : a.seg_rows[2]);
+    seg_col0[wb] = seg == 0 ? a.seg_col0[0] : (seg == 1 ? a.seg_col0[1] : a.seg_col0[2]);
+    const void *seg_w = seg == 0 ? a.seg_w[0] : (seg == 1 ? a.seg_w[1] : a.seg_w[2]);
+    row[wb] = (blk - b0) * 32 + c;
+    wstream[wb] = (const char *)seg_w + ((size_t)(blk - b0) * n_it_total + it_begin) * (size_t)kTileBytes + lane * 16;
+  }
+
+  f32x16_t acc[WB][TB];
+#pragma unroll
+  for (int wb = 0; wb < WB; wb++)
+#pragma unroll
+    for (int t = 0; t < TB; t++)
+#pragma unroll
+      for (int v = 0; v < 16; v++) acc[wb][t][v] = 0.f;
+  u32x4_t ring[2][WB][8];
+  u32x4_t xr[XCH];
+
+  auto load_w = [&](u32x4_t (&dst)[WB][8], int it) {
+#pragma unroll
+    for (int wb = 0; wb < WB; wb++) {
+      const char *p = wstream[wb] + (size_t)it * kTileBytes;
+#pragma unroll
+      for (int j = 0; j < 8; j++) dst[wb][j] = *(const u32x4_t *)(p + j * 1024);
+    }
+  };
+  const char *xbase = (const char *)a.x + (size_t)mt * 128 * a.ldx * sizeof(T);
+  auto load_x = [&](int slab) {
+    const int k0 = k_begin + slab * kSlabIters * KI;
+#pragma unroll
+    for (int i = 0; i < XCH; i++) {
+      const int qq = tid + i * kGemmThreads;
+      const int r = qq / (kSlabRowBytes / 16), cc = qq % (kSlabRowBytes / 16);
+      const int kk = k0 + cc * EPL;
+      xr[i] = *(const u32x4_t *)(xbase + ((size_t)(r < m_loc ? r : 0) * a.ldx + (kk < a.in ? kk : 0)) * sizeof(T));
+    }
+  };
+  auto store_x = [&](int buf) {
+#pragma unroll
+    for (int i = 0; i < XCH; i++) {
+      const int qq = tid + i * kGemmThreads;
+      const int r = qq / (kSlabRowBytes / 16), cc = qq % (kSlabRowBytes / 16);
+      *(u32x4_t *)(lds + buf * kSlabBytes + r * kSlabStride + cc * 16) = xr[i];
+    }
+  };
+  auto compute = [&](const u32x4_t (&w)[WB][8], int buf, int ii) {
+    const unsigned char *base = lds + buf * kSlabBytes + c * kSlabStride + ii * (2 * kLaneBytes) + g * kLaneBytes;
+#pragma unroll
+    for (int j = 0; j < 8; j++) {
+      u32x4_t xf[TB];
+#pragma unroll
+      for (int t = 0; t < TB; t++) xf[t] = *(const u32x4_t *)(base + t * 32 * kSlabStride + j * 16);
+#pragma unroll
+      for (int wb = 0; wb < WB; wb++)
+#pragma unroll
+        for (int t = 0; t < TB; t++) mfma_step(acc[wb][t], xf[t], w[wb][j], T{});
+    }
+  };
+
+  load_x(0);
+  if (0 < n_iter) load_w(ring[0], 0);
+  store_x(0);
+  __syncthreads();
+  // Steady state: a next slab exists, so every load below is unconditional and the compiler can count the
+  // outstanding loads exactly (a guarded load would make it wait for everything before each compute).
+  // The ring stage of iteration it = 2 S + ii is ii.
+  int S = 0;
+  for (; S + 1 < n_slab; S++) {
+    const int buf = S & 1;
+    load_x(S + 1);
+#pragma unroll
+    for (int ii = 0; ii < kSlabIters; ii++) {
+      load_w(ring[(ii + 1) & 1], S * kSlabIters + ii + 1);
+      __builtin_amdgcn_sched_barrier(0);                       // keep the prefetch ahead of the MFMAs
+      compute(ring[ii & 1], buf, ii);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    store_x(buf ^ 1);
+    __syncthreads();
+  }
+  for (; S < n_slab; S++) {                                    // last slab: one or two iterations, nothing follows
+    const int buf = S & 1;
+#pragma unroll
+    for (int ii = 0; ii < kSlabIters; ii++) {
+      const int it = S * kSlabIters + ii;
+      if (it + 1 < n_iter) load_w(ring[(ii + 1) & 1], it + 1);
+      if (it < n_iter) compute(ring[ii & 1], buf, ii);
+    }
+  }
+
+  if (swiglu) {
+    if (!active[0] || row[0] >= seg_rows[0]) return;
+    T *act = (T *)a.act + (size_t)mt * 128 * seg_rows[0] + row[0];
+#pragma unroll
+    for (int t = 0; t < TB; t++)
+#pragma unroll
+      for (int v = 0; v < 16; v++) {
+        const int i = t * 32 + 8 * (v >> 2) + 4 * g + (v & 3);
+        const float gv = acc[0][t][v], uv = acc[1][t][v];
+        if (i < m_loc) act[(size_t)i * seg_rows[0]] = from_f32<T>(gv / (1.0f + expf(-gv)) * uv);
+      }
+    return;
+  }
+#pragma unroll
+  for (int wb = 0; wb < WB; wb++) {
+    if (!active[wb] || row[wb] >= seg_rows[wb]) continue;
+    float *out = a.part + ((size_t)by * a.m_pad + (size_t)mt * 128) * a.ldp + seg_col0[wb] + row[wb];
+#pragma unroll
+    for (int t = 0; t < TB; t++)
+#pragma unroll
+      for (int v = 0; v < 16; v++) {
+        const int i = t * 32 + 8 * (v >> 2) + 4 * g + (v & 3);
+        if (i < m_loc) out[(size_t)i * a.ldp] = acc[wb][t][v];
+      }
+  }
+}
+
 // ---- packing ---------------------------------------------------------------------------------
 // One thread moves one 16-byte piece: dst piece index p = ((rb * n_it + it) * 8 + j) * 64 + lane.
 template <typename T>
@@ -319,7 +471,8 @@ static hipError_t init_t() {
     hipError_t e = hipFuncSetAttribute(fn[tb - 1], hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
   }
-  return hipSuccess;
+  return hipFuncSetAttribute((const void *)gemm_tiled_kernel<T>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                             2 * 4 * 32 * kSlabStride);
 }
 hipError_t gemm_init() {
   static bool done = false;
@@ -340,7 +493,12 @@ static hipError_t launch_t(GemmArgs a, hipStream_t st) {
     a.grid_x = (a.seg_blocks[0] + kGemmWaves / 2 - 1) / (kGemmWaves / 2);
   }
   dim3 grid(a.grid_x, a.n_split);
-  if (a.m_tiles > 1) grid = dim3((a.grid_x * a.n_split + 7) / 8 * 8 * a.m_tiles, 1);   // see the kernel's id decoding
+  if (a.m_tiles > 1) {                                         // two blocks per wave; see gemm_tiled_kernel's id decoding
+    a.grid_x = a.act != nullptr ? (a.seg_blocks[0] + kGemmWaves - 1) / kGemmWaves : (a.total_blocks + 2 * kGemmWaves - 1) / (2 * kGemmWaves);
+    const dim3 tgrid((a.grid_x * a.n_split + 7) / 8 * 8 * a.m_tiles, 1);
+    hipLaunchKernelGGL((gemm_tiled_kernel<T>), tgrid, dim3(kGemmThreads), (size_t)2 * 4 * 32 * kSlabStride, st, a);
+    return hipGetLastError();
+  }
   const size_t lds = (size_t)2 * tb * 32 * kSlabStride;
   if (lds > 160 * 1024) return hipErrorInvalidValue;
   switch (tb) {
