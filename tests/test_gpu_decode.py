@@ -340,6 +340,36 @@ def test_bf16_logits_within_tolerance_of_oracle(env, bf16_model):
     assert p_ok >= 0.99 and p_max < 0.12 and p_rms < 0.02
 
 
+def test_bf16_prefill_in_several_tiles_matches_oracle(env):
+    """A 300-token prompt at 7B width runs the prefill projections as three 128-row tiles (the last one ragged), with
+    SwiGLU formed inside the tiled gate/up launch; the logits of the following verify depend on every cached key and
+    value, and are compared with the bf16-storage oracle like in the test above."""
+    torch, P = env
+    sh = wl.LLAMA2_7B.with_(name="llama2-7b-2layer-p300", n_layers=2, prompt_len=300, gen_tokens=8)
+    hw = wl.make_weights(sh)
+    dw = P.upload_weights(hw, sh.dtype)
+    prompt = wl.make_prompt(sh)
+    eng = P.Engine(sh, dw)
+    first = eng.prefill(prompt)
+    t = eng.draft_tree()
+    eng.verify(t)
+    got = eng.logits(t.n_nodes)
+
+    def oracle_logits(dtype):
+        st, _ = oracle.prefill(as_dtype(hw, dtype), sh, prompt, len(prompt) + 200, dtype=dtype, store=wl.round_to_bf16)
+        ot = oracle.Tree(t.token[:t.n_nodes].copy(), t.parent[:t.n_nodes].copy(), t.depth[:t.n_nodes].copy(), t.score[:t.n_nodes].copy())
+        ot.token[0] = first
+        return np.asarray(oracle.verify_tree(st, ot)[0], dtype=np.float64)
+
+    ref = oracle_logits(np.float64)
+    floor = np.abs(oracle_logits(np.float32) - ref)
+    err = np.abs(got - ref)
+    ok = err <= 3e-2 + 2e-2 * np.abs(ref)
+    print(f"{sh.name}: GPU max err {err.max():.4f} rms {np.sqrt((err ** 2).mean()):.4f}; oracle fp32 max {floor.max():.4f} rms {np.sqrt((floor ** 2).mean()):.4f}")
+    assert ok.mean() >= 0.9999
+    assert err.max() <= max(3e-2, 2.0 * floor.max()) and np.sqrt((err ** 2).mean()) <= max(3e-3, 1.5 * np.sqrt((floor ** 2).mean()))
+
+
 def test_bf16_spec_equals_greedy_bit_exact(env, bf16_model):
     """GPU speculative decoding == GPU plain decoding, token for token and logit bit for logit bit,
     with the real (random) draft and with forged trees that force acceptance."""
