@@ -141,7 +141,11 @@ def main():
 
     # ---- pass A: the timed region ------------------------------------------------------------
     eng = P.Engine(sh, weights, max_seq=max_seq)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
     eng.prefill(prompt)
+    torch.cuda.synchronize()
+    prefill_s = time.perf_counter() - t0                      # not part of `value`: once per request, first call (cold)
     run_cycles(eng, a.warmup)
     # The interpreter's cyclic collector walks every object torch created at import (tens of ms per full
     # collection); park those in the permanent generation so a collection cannot land inside the timed loop.
@@ -185,6 +189,7 @@ def main():
         "mean_accepted_length": emitted / a.steps,
         "plain_decode_tokens_per_s": pe / plain_dt,
         "plain_decode_ms_per_token": plain_dt / a.steps * 1e3,
+        "prefill_ms": prefill_s * 1e3, "prefill_tokens_per_s": sh.prompt_len / prefill_s,
     }
 
     # ---- teacher-forced trees: the same cycles at a paper-like acceptance length (separately labelled) ----
