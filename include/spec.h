@@ -193,7 +193,8 @@ int spec_set_profile(spec_ctx *ctx, int32_t level);
 int spec_get_profile(spec_ctx *ctx, double *ms, int64_t *counts);
 
 /* Message for the last failure on this context ("" if none); valid until the
- * next call on the context.  With ctx == NULL: the last spec_create failure. */
+ * next call on the context.  With ctx == NULL: the last spec_create failure
+ * of the calling thread. */
 const char *spec_last_error(const spec_ctx *ctx);
 
 #ifdef __cplusplus

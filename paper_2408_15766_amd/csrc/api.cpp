@@ -40,7 +40,7 @@ struct HostStage {                    // pinned host staging, one allocation
   int first_token;
 };
 
-std::string g_create_error;
+thread_local std::string g_create_error;   // last spec_create failure of the calling thread
 
 }  // namespace
 
