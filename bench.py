@@ -71,6 +71,15 @@ def run_forced_cycles(eng, n_cycles, stream, pos, accept_per_cycle):
     return emitted, pos, ok
 
 
+def blas_threads():
+    """Threads numpy's matmul uses: the OpenMP/BLAS setting when there is one, else the visible CPUs."""
+    for var in ("OMP_NUM_THREADS", "OPENBLAS_NUM_THREADS", "MKL_NUM_THREADS"):
+        v = os.environ.get(var, "")
+        if v.isdigit() and int(v) > 0:
+            return min(int(v), os.cpu_count() or int(v))
+    return os.cpu_count()
+
+
 def cpu_baseline(sh, layers_timed=2):
     """The oracle as it stands, on the host cores: one draft+verify+accept cycle of a depth-truncated model
     (same widths, same prompt length), plus one decoder layer over the tree rows to extrapolate to full depth."""
@@ -102,7 +111,7 @@ def cpu_baseline(sh, layers_timed=2):
     draft_s, verify_s, layer_s = t1 - t0, t2 - t1, t4 - t3
     full_cycle = draft_s + verify_s + (sh.n_layers - layers_timed) * layer_s
     return {
-        "value": len(emitted) / full_cycle, "unit": "tokens/s", "cores": os.cpu_count(), "kind": "oracle",
+        "value": len(emitted) / full_cycle, "unit": "tokens/s", "cores": blas_threads(), "kind": "oracle",
         "sample": f"1 cycle on a {layers_timed}-layer truncation at full width (draft {draft_s:.2f} s, verify {verify_s:.2f} s), "
                   f"extrapolated to {sh.n_layers} layers with one timed decoder layer ({layer_s:.2f} s); numpy fp32",
         "measured_truncated_cycle_s": draft_s + verify_s,
