@@ -16,7 +16,7 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libspec.so")
 if not os.path.exists(_LIB_PATH):
-    raise ImportError(f"{_LIB_PATH} is missing: build it with `python -m paper_2408_15766_amd.build` "
+    raise ImportError(f"{_LIB_PATH} is missing: build it with `python paper_2408_15766_amd/build.py` "
                       "(there is no fallback path)")
 lib = C.CDLL(_LIB_PATH)
 
@@ -85,6 +85,8 @@ lib.spec_k_attention.argtypes = [C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, 
                                  C.c_int32, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p]
 lib.spec_k_topk_logprob.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
                                     C.c_void_p, C.c_void_p]
+lib.spec_hca_attention.argtypes = [C.c_int32, C.c_void_p, C.POINTER(C.c_void_p), C.POINTER(C.c_void_p), C.c_int32, C.c_int32,
+                                   C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
 
 
 @dataclasses.dataclass
@@ -280,6 +282,26 @@ def spec_k_topk_logprob(logits, k: int):
     if rc:
         raise SpecError(rc, "spec_k_topk_logprob")
     return tok[:, :k], lp[:, :k]
+
+
+def spec_hca_attention(q, ks: Sequence, vs: Sequence, out=None):
+    """q: bf16 torch [batch, seq, hq, hd]; ks[m], vs[m]: bf16 [batch, seq, hkv, hd], one pair per stream
+    (stream 0 = target features, stream m = draft features of training step m).  Returns bf16 [batch, seq, hq, hd]."""
+    import torch
+    n = len(ks)
+    assert len(vs) == n and q.dtype == torch.bfloat16 and q.is_contiguous()
+    assert all(x.dtype == torch.bfloat16 and x.is_contiguous() and x.shape == ks[0].shape for x in list(ks) + list(vs))
+    batch, seq, hq, hd = q.shape
+    hkv = ks[0].shape[2]
+    assert ks[0].shape == (batch, seq, hkv, hd)
+    if out is None:
+        out = torch.empty_like(q)
+    kp = (C.c_void_p * n)(*[x.data_ptr() for x in ks])
+    vp = (C.c_void_p * n)(*[x.data_ptr() for x in vs])
+    rc = lib.spec_hca_attention(n, q.data_ptr(), kp, vp, batch, seq, hq, hkv, hd, out.data_ptr(), _stream_ptr())
+    if rc:
+        raise SpecError(rc, "spec_hca_attention")
+    return out
 
 
 def pack_weights(named_tensors) -> Dict[str, "object"]:

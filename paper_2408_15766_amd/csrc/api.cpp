@@ -865,3 +865,25 @@ int spec_k_topk_logprob(const float *logits, int32_t rows, int32_t vocab, int32_
 }
 
 }  // extern "C"
+
+// ---- training-side entry points (spec_train.h) -----------------------------------------------
+#include "../../include/spec_train.h"
+extern "C" {
+
+int spec_hca_attention(int32_t n_streams, const void *q, const void *const *k, const void *const *v, int32_t batch,
+                       int32_t seq, int32_t hq, int32_t hkv, int32_t hd, void *out, void *stream) {
+  if (!q || !k || !v || !out || n_streams < 1 || n_streams > SPEC_HCA_MAX_STREAMS || batch < 1 || seq < 1) return SPEC_EINVAL;
+  if ((hd != 64 && hd != 128) || hkv < 1 || hq < hkv || hq % hkv) return SPEC_EINVAL;
+  static_assert(SPEC_HCA_MAX_STREAMS == kMaxStreams, "header and kernel agree on the stream limit");
+  HcaArgs a{};
+  a.q = q; a.out = out; a.n_streams = n_streams; a.batch = batch; a.seq = seq; a.hq = hq; a.hkv = hkv; a.hd = hd;
+  a.scale_log2e = (float)(1.4426950408889634 / std::sqrt((double)hd));
+  if (((uintptr_t)q & 15) || ((uintptr_t)out & 15)) return SPEC_EINVAL;
+  for (int m = 0; m < n_streams; m++) {
+    if (!k[m] || !v[m] || ((uintptr_t)k[m] & 15) || ((uintptr_t)v[m] & 15)) return SPEC_EINVAL;
+    a.k[m] = k[m]; a.v[m] = v[m];
+  }
+  return launch_hca_attention(a, (hipStream_t)stream) == hipSuccess ? SPEC_OK : SPEC_EHIP;
+}
+
+}  // extern "C"

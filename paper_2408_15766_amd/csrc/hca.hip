@@ -1,0 +1,305 @@
+// Training attention of harmonized context alignment (Sec. 3.2, appendix A.1) on the matrix cores.
+//
+// Streams m = 0 .. J-1 each hold keys/values for all T positions (stream 0 from the target's features,
+// stream m from the draft features of training step m).  Query t (taken from stream J-1) sees
+//   positions s <= t-(J-1)        from stream 0                      -> the "old" region, and
+//   position  s  = t-o, o <= J-2  from stream J-1-o                  -> the "band": one key per stream.
+// The old region is ordinary causal attention with the diagonal moved J-1 places and runs as a
+// flash-attention loop over blocks of kBlockKeys keys staged in LDS.  The band is J-1 single keys per
+// query, different for every query, and is folded in afterwards by the lanes that own the query.
+//
+// Work decomposition: a workgroup = 4 wavefronts = 128 consecutive queries of one (batch, head); a wavefront
+// owns 32 queries (one MFMA column block).  S^T = K Q^T and O^T = V^T P^T with v_mfma_f32_32x32x16_bf16, so a
+// lane holds, for ITS query (lane % 32), 16 keys of every 32-key tile and 64 of the 128 output dims, and
+// the softmax needs one exchange with lane ^ 32 only.
+#include "common.h"
+#include "kernels.h"
+
+namespace spec {
+
+namespace {
+
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2_t;
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
+typedef __attribute__((ext_vector_type(16))) float f32x16_t;
+
+constexpr int kHcaWaves = 4;
+constexpr int kHcaThreads = kHcaWaves * 64;
+constexpr int kHcaRows = kHcaWaves * 32;      // queries per workgroup
+constexpr int kKeyTiles = 2;                  // 32-key MFMA tiles per staged block
+constexpr int kBlockKeys = 32 * kKeyTiles;
+
+__device__ __forceinline__ f32x16_t mfma16(const u32x4_t &a, const u32x4_t &b, f32x16_t c) {
+  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, a), __builtin_bit_cast(bf16x8_t, b), c, 0, 0, 0);
+}
+__device__ __forceinline__ float lo_f32(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float hi_f32(uint32_t w) { return __uint_as_float(w & 0xFFFF0000u); }
+
+template <int HD> struct HcaLds {
+  static constexpr int kstr = HD * 2 + 16;              // bytes per staged key row (+16: conflict-free b128 reads)
+  static constexpr int vstr = kBlockKeys * 2 + 8;       // bytes per dim row of V^T (+8: conflict-free b64 reads)
+  static constexpr int buf = kBlockKeys * kstr + HD * vstr;
+  static constexpr int total = 2 * buf;                 // double-buffered
+};
+
+template <int HD>
+__global__ __launch_bounds__(kHcaThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void hca_attention_kernel(HcaArgs a) {
+  using L = HcaLds<HD>;
+  constexpr int DB = HD / 32;                 // 32-dim blocks of the output
+  constexpr int KK = HD / 16;                 // MFMA steps of q.k
+  constexpr int PPR = HD * 2 / 16;            // 16-byte pieces per key row
+  constexpr int KP = kBlockKeys * PPR / kHcaThreads;          // K pieces per thread per block
+  constexpr int VP = kBlockKeys / 2 * PPR / kHcaThreads;      // V (key pair, piece) items per thread per block
+  static_assert(kBlockKeys * PPR % kHcaThreads == 0 && (kBlockKeys / 2 * PPR) % kHcaThreads == 0, "staging split");
+  extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+
+  // Workgroup id -> (batch, kv head, head of the group, query tile).  Ids 8 apart run on one XCD: all
+  // tiles and heads that read the same keys/values are placed there, consecutively, longest tile first.
+  const int G = a.hq / a.hkv;
+  const int n_qt = (a.seq + kHcaRows - 1) / kHcaRows;
+  const int per_group = G * n_qt;
+  const int xcd = (int)blockIdx.x & 7, r_id = (int)blockIdx.x >> 3;
+  const int grp = (r_id / per_group) * 8 + xcd;
+  if (grp >= a.batch * a.hkv) return;
+  const int rem = r_id % per_group;
+  const int qt = n_qt - 1 - rem / G, gh = rem % G;
+  const int bi = grp / a.hkv, hk = grp % a.hkv;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, c = lane & 31, g = lane >> 5;
+  const int T = a.seq, J = a.n_streams;
+  const int r0 = qt * kHcaRows + wave * 32;   // first query of the wavefront
+  const int t = r0 + c;
+  const int tq = min(t, T - 1);               // queries past the end compute on the last one and are not stored
+  const int lim = tq - (J - 1);               // last old-region key of this query (may be negative: none)
+  const int wg_lim = min(qt * kHcaRows + kHcaRows - 1, T - 1) - (J - 1);
+  const int nb = wg_lim >= 0 ? wg_lim / kBlockKeys + 1 : 0;
+  const int wave_lim = min(r0 + 31, T - 1) - (J - 1);
+
+  const size_t kv_stride = (size_t)a.hkv * HD;                // elements between consecutive positions
+  const size_t kv_off = (size_t)bi * T * kv_stride + (size_t)hk * HD;
+  const bf16_t *kg = (const bf16_t *)a.k[0] + kv_off;
+  const bf16_t *vg = (const bf16_t *)a.v[0] + kv_off;
+
+  u32x4_t kreg[KP], vreg[VP][2];
+  auto prefetch = [&](int blk) {
+#pragma unroll
+    for (int e = 0; e < KP; e++) {
+      const int q = tid + e * kHcaThreads;
+      // keys past the end of the sequence are masked for every query; they are read from the last position
+      const int key = min(blk * kBlockKeys + q / PPR, T - 1);
+      kreg[e] = *(const u32x4_t *)(kg + (size_t)key * kv_stride + (q % PPR) * 8);
+    }
+#pragma unroll
+    for (int e = 0; e < VP; e++) {
+      const int q = tid + e * kHcaThreads;
+      const int pair = q % (kBlockKeys / 2), piece = q / (kBlockKeys / 2);
+      const int key0 = min(blk * kBlockKeys + 2 * pair, T - 1), key1 = min(blk * kBlockKeys + 2 * pair + 1, T - 1);
+      vreg[e][0] = *(const u32x4_t *)(vg + (size_t)key0 * kv_stride + piece * 8);
+      vreg[e][1] = *(const u32x4_t *)(vg + (size_t)key1 * kv_stride + piece * 8);
+    }
+  };
+  auto stage = [&](int buf) {
+    unsigned char *k_lds = lds + buf * L::buf, *vt_lds = k_lds + kBlockKeys * L::kstr;
+#pragma unroll
+    for (int e = 0; e < KP; e++) {
+      const int q = tid + e * kHcaThreads;
+      *(u32x4_t *)(k_lds + (q / PPR) * L::kstr + (q % PPR) * 16) = kreg[e];
+    }
+#pragma unroll
+    for (int e = 0; e < VP; e++) {                            // V^T[dim][key], two keys per 32-bit store
+      const int q = tid + e * kHcaThreads;
+      const int pair = q % (kBlockKeys / 2), piece = q / (kBlockKeys / 2);
+      const uint32_t w0[4] = {vreg[e][0].x, vreg[e][0].y, vreg[e][0].z, vreg[e][0].w};
+      const uint32_t w1[4] = {vreg[e][1].x, vreg[e][1].y, vreg[e][1].z, vreg[e][1].w};
+#pragma unroll
+      for (int d2 = 0; d2 < 8; d2++) {
+        const uint32_t x = (d2 & 1) ? ((w0[d2 >> 1] >> 16) | (w1[d2 >> 1] & 0xFFFF0000u))
+                                    : ((w0[d2 >> 1] & 0xFFFFu) | (w1[d2 >> 1] << 16));
+        *(uint32_t *)(vt_lds + (piece * 8 + d2) * L::vstr + pair * 4) = x;
+      }
+    }
+  };
+
+  if (nb > 0) prefetch(0);                                    // first block in flight while the queries load
+  // query fragments (B operand): step kk covers dims kk*16 + g*8 .. +8 of query c
+  const bf16_t *qrow = (const bf16_t *)a.q + (((size_t)bi * T + tq) * a.hq + (size_t)hk * G + gh) * HD;
+  u32x4_t qf[KK];
+#pragma unroll
+  for (int kk = 0; kk < KK; kk++) qf[kk] = *(const u32x4_t *)(qrow + kk * 16 + g * 8);
+
+  f32x16_t o[DB];
+#pragma unroll
+  for (int db = 0; db < DB; db++)
+#pragma unroll
+    for (int v = 0; v < 16; v++) o[db][v] = 0.f;
+  // running maximum (of score * scale * log2 e) and sum of 2^(score' - maximum)
+  float m_run = -INFINITY, l_run = 0.f;
+  const float c2 = a.scale_log2e;
+
+  if (nb > 0) {
+    stage(0);
+    __syncthreads();
+    if (nb > 1) prefetch(1);
+  }
+  for (int blk = 0; blk < nb; blk++) {
+    const int cur = blk & 1;
+    const unsigned char *k_lds = lds + cur * L::buf, *vt_lds = k_lds + kBlockKeys * L::kstr;
+    const bool act = blk * kBlockKeys <= wave_lim;            // wavefront-uniform: some query here sees this block
+    uint32_t pk[kKeyTiles][8];                                // probabilities, two bf16 per word
+    if (act) {
+      f32x16_t s[kKeyTiles];
+#pragma unroll
+      for (int kt = 0; kt < kKeyTiles; kt++) {
+#pragma unroll
+        for (int v = 0; v < 16; v++) s[kt][v] = 0.f;
+#pragma unroll
+        for (int kk = 0; kk < KK; kk++) {
+          const u32x4_t kf = *(const u32x4_t *)(k_lds + (kt * 32 + c) * L::kstr + kk * 32 + g * 16);
+          s[kt] = mfma16(kf, qf[kk], s[kt]);
+        }
+      }
+      // s[kt][v] = q . k for key blk*kBlockKeys + kt*32 + 8*(v/4) + 4*g + v%4 and query c
+      if (blk * kBlockKeys + kBlockKeys - 1 > r0 - (J - 1)) {  // the block reaches past some query's region
+        const int key0 = blk * kBlockKeys + 4 * g;
+#pragma unroll
+        for (int kt = 0; kt < kKeyTiles; kt++)
+#pragma unroll
+          for (int v = 0; v < 16; v++)
+            if (key0 + kt * 32 + 8 * (v >> 2) + (v & 3) > lim) s[kt][v] = -INFINITY;
+      }
+      float mb = -INFINITY;
+#pragma unroll
+      for (int kt = 0; kt < kKeyTiles; kt++)
+#pragma unroll
+        for (int v = 0; v < 16; v++) mb = fmaxf(mb, s[kt][v]);
+      mb = fmaxf(mb, __shfl_xor(mb, 32, 64));
+      const float m_new = fmaxf(m_run, mb * c2);
+      const float m_use = m_new == -INFINITY ? 0.f : m_new;    // nothing seen yet: every term below becomes 0
+      const float corr = __builtin_amdgcn_exp2f(m_run - m_use);
+      float ls = 0.f;
+#pragma unroll
+      for (int kt = 0; kt < kKeyTiles; kt++) {
+        float p[16];
+#pragma unroll
+        for (int v = 0; v < 16; v++) { p[v] = __builtin_amdgcn_exp2f(fmaf(s[kt][v], c2, -m_use)); ls += p[v]; }
+#pragma unroll
+        for (int e = 0; e < 8; e++) pk[kt][e] = pack_bf16x2(p[2 * e], p[2 * e + 1]);
+      }
+      ls += __shfl_xor(ls, 32, 64);
+      l_run = l_run * corr + ls;
+      m_run = m_new;
+      if (__any(corr != 1.f)) {
+#pragma unroll
+        for (int db = 0; db < DB; db++)
+#pragma unroll
+          for (int v = 0; v < 16; v++) o[db][v] *= corr;
+      }
+    }
+    if (blk + 1 < nb) {
+      stage(cur ^ 1);                                         // every wavefront left that buffer at the last barrier
+      if (blk + 2 < nb) prefetch(blk + 2);
+    }
+    if (act) {
+      // O^T += V^T P^T in 16-key steps; step (kt, h) uses the lane's own values v = 8h .. 8h+7 of tile kt,
+      // i.e. keys kt*32 + 16h + 8*(e/4) + 4g + e%4, and V^T supplies the same keys per dim.
+#pragma unroll
+      for (int kt = 0; kt < kKeyTiles; kt++)
+#pragma unroll
+        for (int h = 0; h < 2; h++) {
+          const u32x4_t pf = {pk[kt][4 * h], pk[kt][4 * h + 1], pk[kt][4 * h + 2], pk[kt][4 * h + 3]};
+#pragma unroll
+          for (int db = 0; db < DB; db++) {
+            const unsigned char *vp = vt_lds + (db * 32 + c) * L::vstr + (kt * 32 + 16 * h + 4 * g) * 2;
+            const u32x2_t v0 = *(const u32x2_t *)vp, v1 = *(const u32x2_t *)(vp + 16);
+            const u32x4_t vf = {v0.x, v0.y, v1.x, v1.y};
+            o[db] = mfma16(vf, pf, o[db]);
+          }
+        }
+    }
+    __syncthreads();                                          // block blk+1 staged; everyone is done with block blk
+  }
+
+  // The band: key t-off of stream J-1-off, off = 0 .. J-2, oldest first so that keys are visited in
+  // position order.  The lane pair (c, c+32) splits every dot product by dims (the dims of its query
+  // fragments) and every value row by the dims of its output registers.
+  for (int off = J - 2; off >= 0; off--) {
+    const int s_pos = tq - off;
+    const bool have = s_pos >= 0;
+    const size_t row = kv_off + (size_t)(have ? s_pos : 0) * kv_stride;
+    const bf16_t *kb = (const bf16_t *)a.k[J - 1 - off] + row;
+    const bf16_t *vb = (const bf16_t *)a.v[J - 1 - off] + row;
+    float dot = 0.f;
+#pragma unroll
+    for (int kk = 0; kk < KK; kk++) {
+      const u32x4_t kw = *(const u32x4_t *)(kb + kk * 16 + g * 8);
+      const uint32_t kx[4] = {kw.x, kw.y, kw.z, kw.w}, qx[4] = {qf[kk].x, qf[kk].y, qf[kk].z, qf[kk].w};
+#pragma unroll
+      for (int e = 0; e < 4; e++) {
+        dot = fmaf(lo_f32(qx[e]), lo_f32(kx[e]), dot);
+        dot = fmaf(hi_f32(qx[e]), hi_f32(kx[e]), dot);
+      }
+    }
+    dot += __shfl_xor(dot, 32, 64);
+    const float sc = have ? dot * c2 : -INFINITY;
+    const float m_new = fmaxf(m_run, sc);
+    const float m_use = m_new == -INFINITY ? 0.f : m_new;
+    const float corr = __builtin_amdgcn_exp2f(m_run - m_use);
+    const float p = have ? __builtin_amdgcn_exp2f(sc - m_use) : 0.f;
+    l_run = l_run * corr + p;
+    m_run = m_new;
+#pragma unroll
+    for (int db = 0; db < DB; db++)
+#pragma unroll
+      for (int q4 = 0; q4 < 4; q4++) {
+        const u32x2_t vw = *(const u32x2_t *)(vb + db * 32 + 8 * q4 + 4 * g);
+        o[db][4 * q4 + 0] = fmaf(p, lo_f32(vw.x), o[db][4 * q4 + 0] * corr);
+        o[db][4 * q4 + 1] = fmaf(p, hi_f32(vw.x), o[db][4 * q4 + 1] * corr);
+        o[db][4 * q4 + 2] = fmaf(p, lo_f32(vw.y), o[db][4 * q4 + 2] * corr);
+        o[db][4 * q4 + 3] = fmaf(p, hi_f32(vw.y), o[db][4 * q4 + 3] * corr);
+      }
+  }
+
+  if (t >= T) return;
+  const float inv = 1.f / l_run;
+  bf16_t *orow = (bf16_t *)a.out + (((size_t)bi * T + t) * a.hq + (size_t)hk * G + gh) * HD;
+#pragma unroll
+  for (int db = 0; db < DB; db++)
+#pragma unroll
+    for (int q4 = 0; q4 < 4; q4++) {
+      u32x2_t w;
+      w.x = pack_bf16x2(o[db][4 * q4 + 0] * inv, o[db][4 * q4 + 1] * inv);
+      w.y = pack_bf16x2(o[db][4 * q4 + 2] * inv, o[db][4 * q4 + 3] * inv);
+      *(u32x2_t *)(orow + db * 32 + 8 * q4 + 4 * g) = w;
+    }
+}
+
+template <int HD>
+hipError_t launch_hd(const HcaArgs &a, hipStream_t st) {
+  static bool attr_done = false;
+  if (!attr_done) {
+    hipError_t e = hipFuncSetAttribute((const void *)hca_attention_kernel<HD>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       HcaLds<HD>::total);
+    if (e != hipSuccess) return e;
+    attr_done = true;
+  }
+  const int G = a.hq / a.hkv;
+  const int n_qt = (a.seq + kHcaRows - 1) / kHcaRows;
+  const long long groups8 = ((long long)a.batch * a.hkv + 7) / 8;
+  const long long grid = groups8 * 8 * G * n_qt;
+  if (grid > 0x7FFFFFFFll) return hipErrorInvalidValue;
+  hipLaunchKernelGGL((hca_attention_kernel<HD>), dim3((unsigned)grid), dim3(kHcaThreads), HcaLds<HD>::total, st, a);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_hca_attention(const HcaArgs &a, hipStream_t st) {
+  if (a.n_streams < 1 || a.n_streams > kMaxStreams || a.batch < 1 || a.seq < 1 || a.hkv < 1 || a.hq < a.hkv || a.hq % a.hkv)
+    return hipErrorInvalidValue;
+  if (a.hd == 128) return launch_hd<128>(a, st);
+  if (a.hd == 64) return launch_hd<64>(a, st);
+  return hipErrorInvalidValue;
+}
+
+}  // namespace spec

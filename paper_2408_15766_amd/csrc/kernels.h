@@ -83,6 +83,21 @@ struct AttnArgs {
 };
 hipError_t launch_attention(int dtype, const AttnArgs &a, int max_pos, hipStream_t st);
 
+// ---- hca.hip ---------------------------------------------------------------------------------
+// Training attention over J = n_streams key/value streams: query t (from the newest stream) uses, for the key
+// position t - o, stream J-1-o if o <= J-2 and stream 0 otherwise.  bf16 storage.
+// q, out: [batch, seq, hq, hd]; k[m], v[m]: [batch, seq, hkv, hd].
+constexpr int kMaxStreams = 8;
+struct HcaArgs {
+  const void *q;
+  const void *k[kMaxStreams];
+  const void *v[kMaxStreams];
+  void *out;
+  int n_streams, batch, seq, hq, hkv, hd;
+  float scale_log2e;                    // 1/sqrt(hd) * log2(e)
+};
+hipError_t launch_hca_attention(const HcaArgs &a, hipStream_t st);
+
 // ---- select.hip ------------------------------------------------------------------------------
 // argmax over each row of logits [rows, vocab] (ld = vocab), lower index on ties.  Per-slice results go to
 // part_val / part_idx [rows][argmax_slices(vocab)]; if `out` is not null a second kernel merges them into

@@ -204,3 +204,25 @@ def graft_continuation(token, parent, depth, n_nodes: int, continuation) -> int:
     for j in range(1, n):
         depth[j] = depth[par[j]] + 1
     return done
+
+
+def make_hca_streams(seed: int, n_streams: int, batch: int, seq: int, hq: int, hkv: int, hd: int, q_scale: float = 1.0,
+                     drift: float | None = None):
+    """Seeded inputs of the training attention: queries [batch, seq, hq, hd] and, per stream, keys and values
+    [batch, seq, hkv, hd]; float32 arrays whose values are exact in bf16.  Unit-variance normal entries, so
+    q.k / sqrt(hd) has unit variance (q_scale widens it).  drift = None draws every stream independently (the
+    demanding case for a test: a wrong stream changes the output by O(1)); a number makes stream m equal to
+    stream 0 plus m * drift of independent noise, the way draft features sit near the target's.
+    Input preparation only: none of the method's arithmetic."""
+    rng = np.random.Generator(np.random.Philox(key=tensor_seed(seed, f"hca:{n_streams}:{batch}:{seq}:{hq}:{hkv}:{hd}")))
+    q = round_to_bf16(rng.standard_normal((batch, seq, hq, hd), dtype=np.float32) * np.float32(q_scale))
+    ks, vs = [], []
+    for m in range(n_streams):
+        k = rng.standard_normal((batch, seq, hkv, hd), dtype=np.float32)
+        v = rng.standard_normal((batch, seq, hkv, hd), dtype=np.float32)
+        if drift is not None and m > 0:
+            k = ks[0] + np.float32(m * drift) * k
+            v = vs[0] + np.float32(m * drift) * v
+        ks.append(round_to_bf16(k))
+        vs.append(round_to_bf16(v))
+    return q, ks, vs
