@@ -40,8 +40,18 @@ template <int HD> struct HcaLds {
   static constexpr int kstr = HD * 2 + 16;              // bytes per staged key row (+16: conflict-free b128 reads)
   static constexpr int vstr = kBlockKeys * 2 + 8;       // bytes per dim row of V^T (+8: conflict-free b64 reads)
   static constexpr int buf = kBlockKeys * kstr + HD * vstr;
-  static constexpr int total = 2 * buf;                 // double-buffered
+  static constexpr int brow = HD * 2 + 16;              // band scratch: bytes per key (or value) row
+  static constexpr int bwave = 2 * 32 * brow;           // ... per wavefront: 32 key rows + 32 value rows
+  static constexpr int total = 2 * buf > kHcaWaves * bwave ? 2 * buf : kHcaWaves * bwave;   // main loop double-buffered
 };
+
+// Orders this wavefront's LDS writes before its later LDS reads of other lanes' data.  The LDS executes
+// one wavefront's operations in issue order, so only the compiler has to be kept from reordering them.
+__device__ __forceinline__ void wave_lds_order() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
 
 template <int HD>
 __global__ __launch_bounds__(kHcaThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void hca_attention_kernel(HcaArgs a) {
@@ -55,19 +65,29 @@ __global__ __launch_bounds__(kHcaThreads) __attribute__((amdgpu_waves_per_eu(2, 
   extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
 
   // Workgroup id -> (batch, kv head, head of the group, query tile).  Ids 8 apart run on one XCD: all
-  // tiles and heads that read the same keys/values are placed there, consecutively, longest tile first.
+  // tiles and heads that read the same keys/values are placed there, consecutively, longest tile first
+  // (the causal mask makes the last tile the longest).  (With a number of (batch,
+  // kv head) groups that is not a multiple of 8 that placement would leave XCDs idle or uneven; the ids
+  // then simply run group by group.)
   const int G = a.hq / a.hkv;
   const int n_qt = (a.seq + kHcaRows - 1) / kHcaRows;
   const int per_group = G * n_qt;
-  const int xcd = (int)blockIdx.x & 7, r_id = (int)blockIdx.x >> 3;
-  const int grp = (r_id / per_group) * 8 + xcd;
-  if (grp >= a.batch * a.hkv) return;
+  const int n_grp = a.batch * a.hkv;
+  const bool affine = (n_grp & 7) == 0;
+  const int r_id = affine ? (int)blockIdx.x >> 3 : (int)blockIdx.x % per_group;
+  const int grp = affine ? (r_id / per_group) * 8 + ((int)blockIdx.x & 7) : (int)blockIdx.x / per_group;
   const int rem = r_id % per_group;
   const int qt = n_qt - 1 - rem / G, gh = rem % G;
   const int bi = grp / a.hkv, hk = grp % a.hkv;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, c = lane & 31, g = lane >> 5;
   const int T = a.seq, J = a.n_streams;
+  const float c2 = a.scale_log2e;
+  const size_t kv_stride = (size_t)a.hkv * HD;                // elements between consecutive positions
+  const size_t kv_off = (size_t)bi * T * kv_stride + (size_t)hk * HD;
+  const bf16_t *kg = (const bf16_t *)a.k[0] + kv_off;
+  const bf16_t *vg = (const bf16_t *)a.v[0] + kv_off;
+
   const int r0 = qt * kHcaRows + wave * 32;   // first query of the wavefront
   const int t = r0 + c;
   const int tq = min(t, T - 1);               // queries past the end compute on the last one and are not stored
@@ -76,27 +96,49 @@ __global__ __launch_bounds__(kHcaThreads) __attribute__((amdgpu_waves_per_eu(2, 
   const int nb = wg_lim >= 0 ? wg_lim / kBlockKeys + 1 : 0;
   const int wave_lim = min(r0 + 31, T - 1) - (J - 1);
 
-  const size_t kv_stride = (size_t)a.hkv * HD;                // elements between consecutive positions
-  const size_t kv_off = (size_t)bi * T * kv_stride + (size_t)hk * HD;
-  const bf16_t *kg = (const bf16_t *)a.k[0] + kv_off;
-  const bf16_t *vg = (const bf16_t *)a.v[0] + kv_off;
-
+  // Per-thread byte offsets of its pieces inside a key block, computed once; a block's loads are then a
+  // uniform base plus these.  Only a block that reaches past the sequence end needs per-key clamping
+  // (keys past the end are masked for every query; they are read from the last position).
+  constexpr uint32_t kEsz = 2;
+  uint32_t koff[KP], voff[VP];
+#pragma unroll
+  for (int e = 0; e < KP; e++) {
+    const int q = tid + e * kHcaThreads;
+    koff[e] = (uint32_t)((q / PPR) * kv_stride + (q % PPR) * 8) * kEsz;
+  }
+#pragma unroll
+  for (int e = 0; e < VP; e++) {
+    const int q = tid + e * kHcaThreads;
+    voff[e] = (uint32_t)((2 * (q % (kBlockKeys / 2))) * kv_stride + (q / (kBlockKeys / 2)) * 8) * kEsz;
+  }
+  const uint32_t row_bytes = (uint32_t)kv_stride * kEsz;
   u32x4_t kreg[KP], vreg[VP][2];
   auto prefetch = [&](int blk) {
+    const size_t blk_off = (size_t)blk * kBlockKeys * row_bytes;
+    const unsigned char *kbase = (const unsigned char *)kg + blk_off, *vbase = (const unsigned char *)vg + blk_off;
+    if (blk * kBlockKeys + kBlockKeys <= T) {
 #pragma unroll
-    for (int e = 0; e < KP; e++) {
-      const int q = tid + e * kHcaThreads;
-      // keys past the end of the sequence are masked for every query; they are read from the last position
-      const int key = min(blk * kBlockKeys + q / PPR, T - 1);
-      kreg[e] = *(const u32x4_t *)(kg + (size_t)key * kv_stride + (q % PPR) * 8);
-    }
+      for (int e = 0; e < KP; e++) kreg[e] = *(const u32x4_t *)(kbase + koff[e]);
 #pragma unroll
-    for (int e = 0; e < VP; e++) {
-      const int q = tid + e * kHcaThreads;
-      const int pair = q % (kBlockKeys / 2), piece = q / (kBlockKeys / 2);
-      const int key0 = min(blk * kBlockKeys + 2 * pair, T - 1), key1 = min(blk * kBlockKeys + 2 * pair + 1, T - 1);
-      vreg[e][0] = *(const u32x4_t *)(vg + (size_t)key0 * kv_stride + piece * 8);
-      vreg[e][1] = *(const u32x4_t *)(vg + (size_t)key1 * kv_stride + piece * 8);
+      for (int e = 0; e < VP; e++) {
+        vreg[e][0] = *(const u32x4_t *)(vbase + voff[e]);
+        vreg[e][1] = *(const u32x4_t *)(vbase + voff[e] + row_bytes);
+      }
+    } else {
+#pragma unroll
+      for (int e = 0; e < KP; e++) {
+        const int q = tid + e * kHcaThreads;
+        const int key = min(blk * kBlockKeys + q / PPR, T - 1);
+        kreg[e] = *(const u32x4_t *)(kg + (size_t)key * kv_stride + (q % PPR) * 8);
+      }
+#pragma unroll
+      for (int e = 0; e < VP; e++) {
+        const int q = tid + e * kHcaThreads;
+        const int pair = q % (kBlockKeys / 2), piece = q / (kBlockKeys / 2);
+        const int key0 = min(blk * kBlockKeys + 2 * pair, T - 1), key1 = min(blk * kBlockKeys + 2 * pair + 1, T - 1);
+        vreg[e][0] = *(const u32x4_t *)(vg + (size_t)key0 * kv_stride + piece * 8);
+        vreg[e][1] = *(const u32x4_t *)(vg + (size_t)key1 * kv_stride + piece * 8);
+      }
     }
   };
   auto stage = [&](int buf) {
@@ -121,8 +163,17 @@ __global__ __launch_bounds__(kHcaThreads) __attribute__((amdgpu_waves_per_eu(2, 
     }
   };
 
-  if (nb > 0) prefetch(0);                                    // first block in flight while the queries load
-  // query fragments (B operand): step kk covers dims kk*16 + g*8 .. +8 of query c
+  // V^T fragment (A operand) of 16-key step st = 2*tile + half and dim block db: keys step*16 + 4g + {0..3, 8..11}
+  auto vread = [&](const unsigned char *vt_lds, int st, int db) {
+    const unsigned char *vp = vt_lds + (db * 32 + c) * L::vstr + (16 * st + 4 * g) * 2;
+    const u32x2_t v0 = *(const u32x2_t *)vp, v1 = *(const u32x2_t *)(vp + 16);
+    return u32x4_t{v0.x, v0.y, v1.x, v1.y};
+  };
+
+  // query fragments (B operand): step kk covers dims kk*16 + g*8 .. +8 of query c.  They are requested before
+  // the band rows and the first key block: loads complete in order, so once that block has arrived nothing in
+  // the main loop waits on the memory counter for the queries' sake (such a wait would also stall on the
+  // block in flight).
   const bf16_t *qrow = (const bf16_t *)a.q + (((size_t)bi * T + tq) * a.hq + (size_t)hk * G + gh) * HD;
   u32x4_t qf[KK];
 #pragma unroll
@@ -135,9 +186,71 @@ __global__ __launch_bounds__(kHcaThreads) __attribute__((amdgpu_waves_per_eu(2, 
     for (int v = 0; v < 16; v++) o[db][v] = 0.f;
   // running maximum (of score * scale * log2 e) and sum of 2^(score' - maximum)
   float m_run = -INFINITY, l_run = 0.f;
-  const float c2 = a.scale_log2e;
+
+  // The band first (its loads travel together with the first key block's): key t-off of stream J-1-off,
+  // off = J-2 .. 0.  The 32 queries of the wavefront need 32 consecutive rows of that stream: they are read
+  // with coalesced 16-byte accesses (a row = PPR lanes) into the wavefront's own LDS area, and then every
+  // lane pair (c, c+32) picks up the row of ITS query, splitting the dot product by the dims of its query
+  // fragments and the value row by the dims of its output registers.  No other wavefront is involved; the
+  // workgroup barrier below separates this use of the LDS from the key blocks'.
+  {
+    unsigned char *bk = lds + wave * L::bwave, *bv = bk + 32 * L::brow;
+    constexpr int BP = 32 * PPR / 64;                         // 16-byte pieces per lane per tensor
+    for (int off = J - 2; off >= 0; off--) {
+      const bf16_t *kb = (const bf16_t *)a.k[J - 1 - off] + kv_off;
+      const bf16_t *vb = (const bf16_t *)a.v[J - 1 - off] + kv_off;
+      u32x4_t kw_[BP], vw_[BP];
+#pragma unroll
+      for (int e = 0; e < BP; e++) {
+        const int idx = lane + 64 * e;
+        const int row = min(max(r0 + idx / PPR - off, 0), T - 1);
+        kw_[e] = *(const u32x4_t *)(kb + (size_t)row * kv_stride + (idx % PPR) * 8);
+        vw_[e] = *(const u32x4_t *)(vb + (size_t)row * kv_stride + (idx % PPR) * 8);
+      }
+#pragma unroll
+      for (int e = 0; e < BP; e++) {
+        const int idx = lane + 64 * e;
+        *(u32x4_t *)(bk + (idx / PPR) * L::brow + (idx % PPR) * 16) = kw_[e];
+        *(u32x4_t *)(bv + (idx / PPR) * L::brow + (idx % PPR) * 16) = vw_[e];
+      }
+      wave_lds_order();
+      const bool have = tq - off >= 0;
+      float dot = 0.f;
+#pragma unroll
+      for (int kk = 0; kk < KK; kk++) {
+        const u32x4_t kw = *(const u32x4_t *)(bk + c * L::brow + kk * 32 + g * 16);
+        const uint32_t kx[4] = {kw.x, kw.y, kw.z, kw.w}, qx[4] = {qf[kk].x, qf[kk].y, qf[kk].z, qf[kk].w};
+#pragma unroll
+        for (int e = 0; e < 4; e++) {
+          dot = fmaf(lo_f32(qx[e]), lo_f32(kx[e]), dot);
+          dot = fmaf(hi_f32(qx[e]), hi_f32(kx[e]), dot);
+        }
+      }
+      dot += __shfl_xor(dot, 32, 64);
+      const float sc = have ? dot * c2 : -INFINITY;
+      const float m_new = fmaxf(m_run, sc);
+      const float m_use = m_new == -INFINITY ? 0.f : m_new;
+      const float corr = __builtin_amdgcn_exp2f(m_run - m_use);
+      const float p = have ? __builtin_amdgcn_exp2f(sc - m_use) : 0.f;
+      l_run = l_run * corr + p;
+      m_run = m_new;
+#pragma unroll
+      for (int db = 0; db < DB; db++)
+#pragma unroll
+        for (int q4 = 0; q4 < 4; q4++) {
+          const u32x2_t vw = *(const u32x2_t *)(bv + c * L::brow + (db * 32 + 8 * q4 + 4 * g) * 2);
+          o[db][4 * q4 + 0] = fmaf(p, lo_f32(vw.x), o[db][4 * q4 + 0] * corr);
+          o[db][4 * q4 + 1] = fmaf(p, hi_f32(vw.x), o[db][4 * q4 + 1] * corr);
+          o[db][4 * q4 + 2] = fmaf(p, lo_f32(vw.y), o[db][4 * q4 + 2] * corr);
+          o[db][4 * q4 + 3] = fmaf(p, hi_f32(vw.y), o[db][4 * q4 + 3] * corr);
+        }
+      wave_lds_order();                                       // the next stream's rows overwrite the area
+    }
+  }
+  __syncthreads();
 
   if (nb > 0) {
+    prefetch(0);
     stage(0);
     __syncthreads();
     if (nb > 1) prefetch(1);
@@ -174,9 +287,22 @@ __global__ __launch_bounds__(kHcaThreads) __attribute__((amdgpu_waves_per_eu(2, 
 #pragma unroll
         for (int v = 0; v < 16; v++) mb = fmaxf(mb, s[kt][v]);
       mb = fmaxf(mb, __shfl_xor(mb, 32, 64));
-      const float m_new = fmaxf(m_run, mb * c2);
-      const float m_use = m_new == -INFINITY ? 0.f : m_new;    // nothing seen yet: every term below becomes 0
-      const float corr = __builtin_amdgcn_exp2f(m_run - m_use);
+      // The reference maximum moves only when the block's maximum exceeds it by more than 2^8: until then
+      // the probabilities are taken against the old reference (at most 2^8, harmless in fp32 and bf16, and
+      // the final division by the sum cancels the choice), and the 64 output registers are left alone.
+      const float mb2 = mb * c2;
+      const bool move = mb2 > m_run + 8.f;                     // also the first finite maximum after -inf
+      if (__any(move)) {
+        const float m_new = move ? mb2 : m_run;
+        const float corr = move ? __builtin_amdgcn_exp2f(m_run - m_new) : 1.f;   // m_new is finite where move
+        l_run *= corr;
+        m_run = m_new;
+#pragma unroll
+        for (int db = 0; db < DB; db++)
+#pragma unroll
+          for (int v = 0; v < 16; v++) o[db][v] *= corr;
+      }
+      const float m_use = m_run == -INFINITY ? 0.f : m_run;    // nothing seen yet: every term below becomes 0
       float ls = 0.f;
 #pragma unroll
       for (int kt = 0; kt < kKeyTiles; kt++) {
@@ -187,14 +313,7 @@ __global__ __launch_bounds__(kHcaThreads) __attribute__((amdgpu_waves_per_eu(2, 
         for (int e = 0; e < 8; e++) pk[kt][e] = pack_bf16x2(p[2 * e], p[2 * e + 1]);
       }
       ls += __shfl_xor(ls, 32, 64);
-      l_run = l_run * corr + ls;
-      m_run = m_new;
-      if (__any(corr != 1.f)) {
-#pragma unroll
-        for (int db = 0; db < DB; db++)
-#pragma unroll
-          for (int v = 0; v < 16; v++) o[db][v] *= corr;
-      }
+      l_run += ls;
     }
     if (blk + 1 < nb) {
       stage(cur ^ 1);                                         // every wavefront left that buffer at the last barrier
@@ -204,60 +323,14 @@ __global__ __launch_bounds__(kHcaThreads) __attribute__((amdgpu_waves_per_eu(2, 
       // O^T += V^T P^T in 16-key steps; step (kt, h) uses the lane's own values v = 8h .. 8h+7 of tile kt,
       // i.e. keys kt*32 + 16h + 8*(e/4) + 4g + e%4, and V^T supplies the same keys per dim.
 #pragma unroll
-      for (int kt = 0; kt < kKeyTiles; kt++)
+      for (int st = 0; st < 2 * kKeyTiles; st++) {
+        const int kt = st >> 1, h = st & 1;
+        const u32x4_t pf = {pk[kt][4 * h], pk[kt][4 * h + 1], pk[kt][4 * h + 2], pk[kt][4 * h + 3]};
 #pragma unroll
-        for (int h = 0; h < 2; h++) {
-          const u32x4_t pf = {pk[kt][4 * h], pk[kt][4 * h + 1], pk[kt][4 * h + 2], pk[kt][4 * h + 3]};
-#pragma unroll
-          for (int db = 0; db < DB; db++) {
-            const unsigned char *vp = vt_lds + (db * 32 + c) * L::vstr + (kt * 32 + 16 * h + 4 * g) * 2;
-            const u32x2_t v0 = *(const u32x2_t *)vp, v1 = *(const u32x2_t *)(vp + 16);
-            const u32x4_t vf = {v0.x, v0.y, v1.x, v1.y};
-            o[db] = mfma16(vf, pf, o[db]);
-          }
-        }
+        for (int db = 0; db < DB; db++) o[db] = mfma16(vread(vt_lds, st, db), pf, o[db]);
+      }
     }
     __syncthreads();                                          // block blk+1 staged; everyone is done with block blk
-  }
-
-  // The band: key t-off of stream J-1-off, off = 0 .. J-2, oldest first so that keys are visited in
-  // position order.  The lane pair (c, c+32) splits every dot product by dims (the dims of its query
-  // fragments) and every value row by the dims of its output registers.
-  for (int off = J - 2; off >= 0; off--) {
-    const int s_pos = tq - off;
-    const bool have = s_pos >= 0;
-    const size_t row = kv_off + (size_t)(have ? s_pos : 0) * kv_stride;
-    const bf16_t *kb = (const bf16_t *)a.k[J - 1 - off] + row;
-    const bf16_t *vb = (const bf16_t *)a.v[J - 1 - off] + row;
-    float dot = 0.f;
-#pragma unroll
-    for (int kk = 0; kk < KK; kk++) {
-      const u32x4_t kw = *(const u32x4_t *)(kb + kk * 16 + g * 8);
-      const uint32_t kx[4] = {kw.x, kw.y, kw.z, kw.w}, qx[4] = {qf[kk].x, qf[kk].y, qf[kk].z, qf[kk].w};
-#pragma unroll
-      for (int e = 0; e < 4; e++) {
-        dot = fmaf(lo_f32(qx[e]), lo_f32(kx[e]), dot);
-        dot = fmaf(hi_f32(qx[e]), hi_f32(kx[e]), dot);
-      }
-    }
-    dot += __shfl_xor(dot, 32, 64);
-    const float sc = have ? dot * c2 : -INFINITY;
-    const float m_new = fmaxf(m_run, sc);
-    const float m_use = m_new == -INFINITY ? 0.f : m_new;
-    const float corr = __builtin_amdgcn_exp2f(m_run - m_use);
-    const float p = have ? __builtin_amdgcn_exp2f(sc - m_use) : 0.f;
-    l_run = l_run * corr + p;
-    m_run = m_new;
-#pragma unroll
-    for (int db = 0; db < DB; db++)
-#pragma unroll
-      for (int q4 = 0; q4 < 4; q4++) {
-        const u32x2_t vw = *(const u32x2_t *)(vb + db * 32 + 8 * q4 + 4 * g);
-        o[db][4 * q4 + 0] = fmaf(p, lo_f32(vw.x), o[db][4 * q4 + 0] * corr);
-        o[db][4 * q4 + 1] = fmaf(p, hi_f32(vw.x), o[db][4 * q4 + 1] * corr);
-        o[db][4 * q4 + 2] = fmaf(p, lo_f32(vw.y), o[db][4 * q4 + 2] * corr);
-        o[db][4 * q4 + 3] = fmaf(p, hi_f32(vw.y), o[db][4 * q4 + 3] * corr);
-      }
   }
 
   if (t >= T) return;
@@ -285,8 +358,7 @@ hipError_t launch_hd(const HcaArgs &a, hipStream_t st) {
   }
   const int G = a.hq / a.hkv;
   const int n_qt = (a.seq + kHcaRows - 1) / kHcaRows;
-  const long long groups8 = ((long long)a.batch * a.hkv + 7) / 8;
-  const long long grid = groups8 * 8 * G * n_qt;
+  const long long grid = (long long)a.batch * a.hkv * G * n_qt;
   if (grid > 0x7FFFFFFFll) return hipErrorInvalidValue;
   hipLaunchKernelGGL((hca_attention_kernel<HD>), dim3((unsigned)grid), dim3(kHcaThreads), HcaLds<HD>::total, st, a);
   return hipGetLastError();
