@@ -5,7 +5,8 @@ One "step" is one draft + verify + accept cycle (all hot-path stages) at batch 1
 synthetic random-init LLaMA2-7B-shaped model (bf16, prompt 512, dynamic tree depth 6 / top-k 10 /
 60 verified tokens).  Prints ONE JSON line: tokens/s over exactly --steps cycles, the roofline of the
 dominant kernel (the weight-streaming GEMM, timed with HIP events in a separate instrumented pass),
-and the CPU oracle timed on a bounded sample of the same workload.
+and the CPU oracle timed on a bounded sample of the same workload.  A separately labelled object
+(`hca_attention`) measures the training-side attention kernel against the matrix-core peak.
 """
 from __future__ import annotations
 
@@ -37,6 +38,7 @@ def parse():
                     help="draft tokens accepted per cycle in the teacher-forced extra pass (0 = skip the pass)")
     ap.add_argument("--tree", default="", help="override the draft tree as depth,topk,total (default: the config's 6,10,60)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-hca", action="store_true", help="skip the training-attention measurement (separate object in the JSON line)")
     ap.add_argument("--no-roofline-pass", action="store_true", help="skip the instrumented passes (for profilers)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain 1 GiB device copy four times (known traffic, to scale rocprofv3's FETCH_SIZE/WRITE_SIZE)")
@@ -116,6 +118,54 @@ def cpu_baseline(sh, layers_timed=2):
                   f"extrapolated to {sh.n_layers} layers with one timed decoder layer ({layer_s:.2f} s); numpy fp32",
         "measured_truncated_cycle_s": draft_s + verify_s,
     }
+
+
+MFMA_BF16_PEAK_TFLOPS = 2500.0
+
+
+def hca_attention_bench(sh, with_cpu, launches=50):
+    """Training attention of harmonized context alignment (Sec. 3.2) at the training launch the appendix (Training
+    Overhead) describes: batch 2, three aligning steps, 2048 positions, the draft layer's head layout.  Algorithmic
+    flop = 4 * head_dim per (query, visible key) pair; timed with events on the stream the kernel is launched on,
+    `launches` launches per event pair."""
+    import numpy as np
+    import torch
+    import workload as wl
+    import paper_2408_15766_amd as P
+    n_streams, batch, seq = 3, 2, 2048
+    hq, hkv, hd = sh.n_q_heads, sh.n_kv_heads, sh.head_dim
+    q, ks, vs = wl.make_hca_streams(sh.seed, n_streams, batch, seq, hq, hkv, hd, drift=0.3)
+    dev = lambda x: torch.from_numpy(x).cuda().to(torch.bfloat16)
+    dq, dks, dvs = dev(q), [dev(k) for k in ks], [dev(v) for v in vs]
+    out = torch.empty_like(dq)
+    for _ in range(5):
+        P.spec_hca_attention(dq, dks, dvs, out)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(launches):
+        P.spec_hca_attention(dq, dks, dvs, out)
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / launches
+    flop = 4.0 * hd * hq * batch * (seq * (seq + 1) / 2)
+    res = {"workload": f"{sh.name} draft layer: batch {batch} x {seq} positions, {n_streams} streams, {hq} query / {hkv} kv heads of {hd}",
+           "dtype": "bf16", "ms_per_launch": ms, "launches": launches,
+           "roofline": {"bound": "mfma", "achieved": flop / (ms * 1e-3) / 1e12, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                        "frac": flop / (ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
+                        "kernel": "hca_attention_kernel", "algorithmic_flop_per_launch": flop}}
+    if with_cpu:
+        from oracle import hca
+        heads = sorted({0, hq // 3, 2 * hq // 3, hq - 1})
+        f64 = lambda x: x[0].astype(np.float64)
+        t0 = time.perf_counter()
+        want = hca.hca_attention(f64(q), [f64(k) for k in ks], [f64(v) for v in vs], heads=heads)
+        dt = time.perf_counter() - t0
+        got = out[0].float().cpu().numpy()[:, heads]
+        res["cpu_baseline"] = {"value": flop * len(heads) / (hq * batch) / dt / 1e12, "unit": "TFLOP/s", "cores": blas_threads(),
+                               "kind": "oracle", "sample": f"{len(heads)} of {hq * batch} (batch, head) pairs, numpy fp64, {dt:.2f} s"}
+        res["max_abs_diff_vs_oracle_sample"] = float(np.abs(got - want[:, heads]).max())
+    return res
 
 
 def main():
@@ -248,6 +298,8 @@ def main():
                                    "kernel": "gemm_stream_kernel (verify launches)", "launches_per_step": n_launch,
                                    "avg_launch_ms": avg_ms, "event_interval_ms": raw_ms, "empty_event_pair_ms": pair_ms,
                                    "algorithmic_bytes_per_launch": bytes_per_launch}
+    if not a.no_hca:
+        out["hca_attention"] = hca_attention_bench(wl.BY_NAME[a.config], not a.no_cpu_baseline)
     if not a.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl.BY_NAME[a.config])
     print(json.dumps(out))
