@@ -38,6 +38,36 @@ extern "C" {
 int spec_hca_attention(int32_t n_streams, const void *q, const void *const *k, const void *const *v, int32_t batch,
                        int32_t seq, int32_t hq, int32_t hkv, int32_t hd, void *out, void *stream);
 
+#define SPEC_LOSS_MAX_K 128
+
+/* Top-K distillation loss of harmonized objective distillation (Sec. 3.1,
+ * Eq. 1), computed from features through the shared LM head, together with the
+ * cross-entropy term of the Sec. 3.2 objective.  For each of `rows` positions r
+ *     zq = lm_head . feat_target[r],   zp = lm_head . feat_draft[r]     (fp32 accumulation)
+ *     q = softmax(zq),  p = softmax(zp),  Omega-hat = the k tokens of largest q
+ *                                         (equal q: lower token id)
+ *     loss_topk[r] = - sum over Omega-hat of q(x) log p(x)              (Eq. 1)
+ *     loss_ce[r]   = - sum over the vocabulary of q(x) log p(x)
+ * and loss_sum[0] = sum_r loss_topk[r], loss_sum[1] = sum_r loss_ce[r] (fixed
+ * order; the mean over positions and the weight w of Sec. 4.1 are the
+ * caller's).  K = 10 in the paper; 1 <= k <= SPEC_LOSS_MAX_K, k <= vocab,
+ * ceil(vocab / 4096) * k <= 4096.
+ *
+ * feat_target, feat_draft: [rows, d] in dtype (SPEC_DTYPE_FP32 / _BF16), row
+ * stride d.  lm_head: [vocab, d] in the PACKED layout of spec_pack_weight, same
+ * dtype.  Outputs fp32: loss_topk, loss_ce [rows]; loss_sum [2] (any of the
+ * three may be NULL).  scratch: spec_topk_loss_scratch_bytes(rows, vocab, k)
+ * bytes of device memory, 256-byte aligned, owned by the caller; it holds the
+ * fp32 logits of at most 512 positions at a time (sized to stay in the
+ * last-level cache between the GEMM and the loss kernels) and per-slice
+ * candidates.  The logits themselves are
+ * not returned.  Errors: SPEC_EINVAL for bad arguments or a scratch that is too
+ * small (nothing is launched), SPEC_EHIP if a launch fails. */
+uint64_t spec_topk_loss_scratch_bytes(int32_t rows, int32_t vocab, int32_t k);
+int spec_topk_loss(int32_t dtype, const void *feat_target, const void *feat_draft, int32_t rows, int32_t d,
+                   const void *lm_head, int32_t vocab, int32_t k, void *scratch, uint64_t scratch_bytes, float *loss_topk,
+                   float *loss_ce, float *loss_sum, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -87,6 +87,10 @@ lib.spec_k_topk_logprob.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32,
                                     C.c_void_p, C.c_void_p]
 lib.spec_hca_attention.argtypes = [C.c_int32, C.c_void_p, C.POINTER(C.c_void_p), C.POINTER(C.c_void_p), C.c_int32, C.c_int32,
                                    C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
+lib.spec_topk_loss_scratch_bytes.restype = C.c_uint64
+lib.spec_topk_loss_scratch_bytes.argtypes = [C.c_int32, C.c_int32, C.c_int32]
+lib.spec_topk_loss.argtypes = [C.c_int32, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_int32, C.c_int32,
+                               C.c_void_p, C.c_uint64, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
 
 
 @dataclasses.dataclass
@@ -302,6 +306,34 @@ def spec_hca_attention(q, ks: Sequence, vs: Sequence, out=None):
     if rc:
         raise SpecError(rc, "spec_hca_attention")
     return out
+
+
+def spec_topk_loss_scratch_bytes(rows: int, vocab: int, k: int) -> int:
+    return int(lib.spec_topk_loss_scratch_bytes(rows, vocab, k))
+
+
+def spec_topk_loss(feat_target, feat_draft, lm_head_packed, k: int, scratch=None):
+    """feat_target, feat_draft: torch [rows, d] (bf16 or fp32); lm_head_packed: the LM head after spec_pack_weight.
+    Returns (loss_topk [rows], loss_ce [rows], loss_sum [2]) as fp32 torch tensors."""
+    import torch
+    assert feat_target.shape == feat_draft.shape and feat_target.dtype == feat_draft.dtype
+    assert feat_target.is_contiguous() and feat_draft.is_contiguous()
+    dtype = 1 if feat_target.dtype == torch.bfloat16 else 0
+    rows, d = feat_target.shape
+    vocab = lm_head_packed.logical_shape[0]
+    n = spec_topk_loss_scratch_bytes(rows, vocab, k)
+    if n == 0:
+        raise SpecError(SPEC_EINVAL, f"spec_topk_loss: rows {rows}, vocab {vocab}, k {k} not supported")
+    if scratch is None:
+        scratch = torch.empty(n, dtype=torch.uint8, device=feat_target.device)
+    topk = torch.empty(rows, dtype=torch.float32, device=feat_target.device)
+    ce = torch.empty(rows, dtype=torch.float32, device=feat_target.device)
+    tot = torch.empty(2, dtype=torch.float32, device=feat_target.device)
+    rc = lib.spec_topk_loss(dtype, feat_target.data_ptr(), feat_draft.data_ptr(), rows, d, lm_head_packed.data_ptr(), vocab, k,
+                            scratch.data_ptr(), scratch.numel(), topk.data_ptr(), ce.data_ptr(), tot.data_ptr(), _stream_ptr())
+    if rc:
+        raise SpecError(rc, "spec_topk_loss")
+    return topk, ce, tot
 
 
 def pack_weights(named_tensors) -> Dict[str, "object"]:

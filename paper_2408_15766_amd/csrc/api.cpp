@@ -886,4 +886,65 @@ int spec_hca_attention(int32_t n_streams, const void *q, const void *const *k, c
   return launch_hca_attention(a, (hipStream_t)stream) == hipSuccess ? SPEC_OK : SPEC_EHIP;
 }
 
+namespace {
+constexpr int kLossChunk = 512;                               // positions whose logits are live at a time
+struct LossLayout { int chunk, ldz; size_t zq, zp, cand, rows_topk, rows_ce, total; };   // offsets in floats
+LossLayout loss_layout(int rows, int vocab, int k) {
+  LossLayout l{};
+  l.chunk = rows < kLossChunk ? rows : kLossChunk;
+  l.ldz = (vocab + 63) / 64 * 64;
+  auto up = [](size_t x) { return (x + 63) / 64 * 64; };
+  size_t o = 0;
+  l.zq = o; o += up((size_t)l.chunk * l.ldz);
+  l.zp = o; o += up((size_t)l.chunk * l.ldz);
+  l.cand = o; o += up(topk_loss_scratch_floats(l.chunk, vocab, k));
+  l.rows_topk = o; o += up((size_t)rows);                     // used when the caller does not want the per-row losses
+  l.rows_ce = o; o += up((size_t)rows);
+  l.total = o;
+  return l;
+}
+bool loss_args_ok(int rows, int vocab, int k) {
+  return rows >= 1 && vocab >= 1 && k >= 1 && k <= SPEC_LOSS_MAX_K && k <= vocab && (int64_t)((vocab + kTopkSlice - 1) / kTopkSlice) * k <= 4096;
+}
+}  // namespace
+
+uint64_t spec_topk_loss_scratch_bytes(int32_t rows, int32_t vocab, int32_t k) {
+  if (!loss_args_ok(rows, vocab, k)) return 0;
+  return (uint64_t)loss_layout(rows, vocab, k).total * sizeof(float);
+}
+
+int spec_topk_loss(int32_t dtype, const void *feat_target, const void *feat_draft, int32_t rows, int32_t d,
+                   const void *lm_head, int32_t vocab, int32_t k, void *scratch, uint64_t scratch_bytes, float *loss_topk,
+                   float *loss_ce, float *loss_sum, void *stream) {
+  static_assert(SPEC_LOSS_MAX_K == kLossMaxK, "header and kernel agree on the K limit");
+  if (!feat_target || !feat_draft || !lm_head || !scratch || (dtype != 0 && dtype != 1) || !loss_args_ok(rows, vocab, k))
+    return SPEC_EINVAL;
+  const int epl = dtype == 1 ? 8 : 4;
+  if (d < 1 || d % epl || ((uintptr_t)scratch & 255)) return SPEC_EINVAL;
+  const LossLayout l = loss_layout(rows, vocab, k);
+  if (scratch_bytes < (uint64_t)l.total * sizeof(float)) return SPEC_EINVAL;
+  float *sf = (float *)scratch;
+  float *out_topk = loss_topk ? loss_topk : sf + l.rows_topk, *out_ce = loss_ce ? loss_ce : sf + l.rows_ce;
+  const size_t esz = dtype == 1 ? 2 : 4;
+  hipStream_t st = (hipStream_t)stream;
+  for (int r0 = 0; r0 < rows; r0 += l.chunk) {
+    const int m = rows - r0 < l.chunk ? rows - r0 : l.chunk;
+    const void *xs[2] = {(const char *)feat_target + (size_t)r0 * d * esz, (const char *)feat_draft + (size_t)r0 * d * esz};
+    float *zs[2] = {sf + l.zq, sf + l.zp};
+    for (int side = 0; side < 2; side++) {                    // the LM head over the chunk's rows: fp32 logits
+      GemmArgs a{};
+      a.x = xs[side]; a.ldx = d; a.m = m; a.in = d;
+      for (int s = 0; s < 3; s++) { a.seg_w[s] = lm_head; a.seg_rows[s] = 0; a.seg_blocks[s] = 0; a.seg_col0[s] = 0; }
+      a.seg_rows[0] = vocab; a.seg_blocks[0] = (vocab + 31) / 32;
+      a.nseg = 1; a.total_blocks = a.seg_blocks[0];
+      a.part = zs[side]; a.ldp = l.ldz; a.m_pad = l.chunk; a.n_split = 1;
+      if (launch_gemm(dtype, a, st) != hipSuccess) return SPEC_EHIP;
+    }
+    if (launch_topk_loss_rows(zs[0], zs[1], l.ldz, m, vocab, k, sf + l.cand, out_topk + r0, out_ce + r0, st) != hipSuccess)
+      return SPEC_EHIP;
+  }
+  if (loss_sum && launch_loss_total(out_topk, out_ce, rows, loss_sum, st) != hipSuccess) return SPEC_EHIP;
+  return SPEC_OK;
+}
+
 }  // extern "C"

@@ -98,6 +98,18 @@ struct HcaArgs {
 };
 hipError_t launch_hca_attention(const HcaArgs &a, hipStream_t st);
 
+// ---- distill.hip -----------------------------------------------------------------------------
+// Per position, from fp32 logit rows zq (target) and zp (draft), row stride ldz:
+//   loss_topk = - sum over the k tokens of largest zq of softmax(zq) * log_softmax(zp)   (lower token id on ties)
+//   loss_ce   = the same sum over the whole vocabulary.
+// scratch: topk_loss_scratch_floats(rows, vocab, k) floats.  rows <= 65535, k <= kLossMaxK, ceil(vocab/4096)*k <= 4096.
+constexpr int kLossMaxK = 128;
+size_t topk_loss_scratch_floats(int rows, int vocab, int k);
+hipError_t launch_topk_loss_rows(const float *zq, const float *zp, int ldz, int rows, int vocab, int k, float *scratch,
+                                 float *loss_topk, float *loss_ce, hipStream_t st);
+// out[0] = sum of loss_topk[0..rows), out[1] = sum of loss_ce[0..rows), in a fixed order.
+hipError_t launch_loss_total(const float *loss_topk, const float *loss_ce, int rows, float *out, hipStream_t st);
+
 // ---- select.hip ------------------------------------------------------------------------------
 // argmax over each row of logits [rows, vocab] (ld = vocab), lower index on ties.  Per-slice results go to
 // part_val / part_idx [rows][argmax_slices(vocab)]; if `out` is not null a second kernel merges them into

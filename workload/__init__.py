@@ -226,3 +226,23 @@ def make_hca_streams(seed: int, n_streams: int, batch: int, seq: int, hq: int, h
         ks.append(round_to_bf16(k))
         vs.append(round_to_bf16(v))
     return q, ks, vs
+
+
+def make_distill_inputs(seed: int, rows: int, d: int, vocab: int, dtype: str, drift: float = 0.5, tie_halves: bool = False,
+                        logit_std: float = 3.0):
+    """Seeded inputs of the distillation loss: target features [rows, d] (unit-variance normal, as after a final
+    norm), draft features = target + drift * independent noise (a draft model's estimate), LM head [vocab, d]
+    normal with the spread that gives logits of standard deviation logit_std (a peaked next-token distribution:
+    the best token of 32000 holds a few percent to tens of percent of the mass, the way a language model's does);
+    float32 arrays, exact in bf16 when dtype == "bf16".  tie_halves repeats the first half of the LM head in the
+    second half, so that every logit occurs twice (exact ties).
+    Input preparation only: none of the method's arithmetic."""
+    rng = np.random.Generator(np.random.Philox(key=tensor_seed(seed, f"distill:{rows}:{d}:{vocab}:{dtype}")))
+    ft = rng.standard_normal((rows, d), dtype=np.float32)
+    fd = ft + np.float32(drift) * rng.standard_normal((rows, d), dtype=np.float32)
+    w = rng.standard_normal((vocab, d), dtype=np.float32) * np.float32(logit_std / np.sqrt(d))
+    if tie_halves:
+        w[vocab // 2: 2 * (vocab // 2)] = w[: vocab // 2]
+    if dtype == "bf16":
+        ft, fd, w = round_to_bf16(ft), round_to_bf16(fd), round_to_bf16(w)
+    return ft, fd, w
