@@ -5,8 +5,9 @@ One "step" is one draft + verify + accept cycle (all hot-path stages) at batch 1
 synthetic random-init LLaMA2-7B-shaped model (bf16, prompt 512, dynamic tree depth 6 / top-k 10 /
 60 verified tokens).  Prints ONE JSON line: tokens/s over exactly --steps cycles, the roofline of the
 dominant kernel (the weight-streaming GEMM, timed with HIP events in a separate instrumented pass),
-and the CPU oracle timed on a bounded sample of the same workload.  A separately labelled object
-(`hca_attention`) measures the training-side attention kernel against the matrix-core peak.
+and the CPU oracle timed on a bounded sample of the same workload.  Two separately labelled
+objects measure the training-side kernels against the matrix-core peak: `hca_attention` (Sec. 3.2) and `topk_loss`
+(Sec. 3.1).
 """
 from __future__ import annotations
 
@@ -39,6 +40,7 @@ def parse():
     ap.add_argument("--tree", default="", help="override the draft tree as depth,topk,total (default: the config's 6,10,60)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-hca", action="store_true", help="skip the training-attention measurement (separate object in the JSON line)")
+    ap.add_argument("--no-loss", action="store_true", help="skip the distillation-loss measurement (separate object in the JSON line)")
     ap.add_argument("--no-roofline-pass", action="store_true", help="skip the instrumented passes (for profilers)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain 1 GiB device copy four times (known traffic, to scale rocprofv3's FETCH_SIZE/WRITE_SIZE)")
@@ -165,6 +167,56 @@ def hca_attention_bench(sh, with_cpu, launches=50):
         res["cpu_baseline"] = {"value": flop * len(heads) / (hq * batch) / dt / 1e12, "unit": "TFLOP/s", "cores": blas_threads(),
                                "kind": "oracle", "sample": f"{len(heads)} of {hq * batch} (batch, head) pairs, numpy fp64, {dt:.2f} s"}
         res["max_abs_diff_vs_oracle_sample"] = float(np.abs(got - want[:, heads]).max())
+    return res
+
+
+def topk_loss_bench(sh, with_cpu, launches=5):
+    """Top-K distillation loss through the LM head (Sec. 3.1, Eq. 1; K = 10) for the positions of one training batch
+    (batch 2 x 2048, appendix Training Overhead): two LM-head GEMMs of 4096 rows (target and draft features) plus the
+    loss kernels.  Algorithmic flop = 2 * (2 * rows) * vocab * d (the loss arithmetic itself is not counted)."""
+    import numpy as np
+    import torch
+    import workload as wl
+    import paper_2408_15766_amd as P
+    rows, d, vocab, k = 2 * 2048, sh.d_model, sh.vocab, 10
+    host = vocab * d <= 2e8                                   # larger heads are drawn on the device; no CPU sample then
+    if host:
+        ft, fd, w = wl.make_distill_inputs(sh.seed, rows, d, vocab, "bf16")
+        dft, dfd, dw = (torch.from_numpy(x).cuda().to(torch.bfloat16) for x in (ft, fd, w))
+    else:
+        g = torch.Generator(device="cuda").manual_seed(sh.seed)
+        dft = torch.randn((rows, d), device="cuda", generator=g).to(torch.bfloat16)
+        dfd = (dft.float() + 0.5 * torch.randn((rows, d), device="cuda", generator=g)).to(torch.bfloat16)
+        dw = (torch.randn((vocab, d), device="cuda", generator=g) * (3.0 / d ** 0.5)).to(torch.bfloat16)
+    head = P.spec_pack_weight(dw)
+    del dw
+    scratch = torch.empty(P.spec_topk_loss_scratch_bytes(rows, vocab, k), dtype=torch.uint8, device="cuda")
+    for _ in range(2):
+        topk, ce, tot = P.spec_topk_loss(dft, dfd, head, k, scratch)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(launches):
+        P.spec_topk_loss(dft, dfd, head, k, scratch)
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / launches
+    flop = 2.0 * (2 * rows) * vocab * d
+    res = {"workload": f"{sh.name} LM head: {rows} positions (batch 2 x 2048), d {d}, vocabulary {vocab}, K {k}",
+           "dtype": "bf16", "ms_per_call": ms, "calls": launches, "mean_topk_loss": float(tot[0]) / rows, "mean_cross_entropy": float(tot[1]) / rows,
+           "roofline": {"bound": "mfma", "achieved": flop / (ms * 1e-3) / 1e12, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                        "frac": flop / (ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
+                        "kernel": "gemm_tiled_kernel (LM head, 512-row chunks) + loss_slice_kernel + loss_merge_kernel",
+                        "algorithmic_flop_per_call": flop}}
+    if with_cpu and host:
+        from oracle import distill
+        sample = np.arange(0, rows, rows // 16)
+        t0 = time.perf_counter()
+        want, want_ce = distill.head_losses(ft[sample].astype(np.float64), fd[sample].astype(np.float64), w.astype(np.float64), k)
+        dt = time.perf_counter() - t0
+        res["cpu_baseline"] = {"value": flop * len(sample) / rows / dt / 1e12, "unit": "TFLOP/s", "cores": blas_threads(), "kind": "oracle",
+                               "sample": f"{len(sample)} of {rows} positions, numpy fp64, {dt:.2f} s"}
+        res["max_abs_diff_vs_oracle_sample"] = float(np.abs(topk.cpu().numpy()[sample] - want).max())
     return res
 
 
@@ -300,6 +352,11 @@ def main():
                                    "algorithmic_bytes_per_launch": bytes_per_launch}
     if not a.no_hca:
         out["hca_attention"] = hca_attention_bench(wl.BY_NAME[a.config], not a.no_cpu_baseline)
+    if not a.no_loss:
+        del weights
+        gc.collect()
+        torch.cuda.empty_cache()
+        out["topk_loss"] = topk_loss_bench(wl.BY_NAME[a.config], not a.no_cpu_baseline)
     if not a.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl.BY_NAME[a.config])
     print(json.dumps(out))
