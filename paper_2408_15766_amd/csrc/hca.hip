@@ -259,7 +259,12 @@ __global__ __launch_bounds__(kHcaThreads) __attribute__((amdgpu_waves_per_eu(2, 
     const int cur = blk & 1;
     const unsigned char *k_lds = lds + cur * L::buf, *vt_lds = k_lds + kBlockKeys * L::kstr;
     const bool act = blk * kBlockKeys <= wave_lim;            // wavefront-uniform: some query here sees this block
-    uint32_t pk[kKeyTiles][8];                                // probabilities, two bf16 per word
+    // The next block is staged first (into the buffer every wavefront left at the last barrier), from the
+    // registers its loads filled during the previous iteration; the loads of the block after it follow.
+    if (blk + 1 < nb) {
+      stage(cur ^ 1);
+      if (blk + 2 < nb) prefetch(blk + 2);
+    }
     if (act) {
       f32x16_t s[kKeyTiles];
 #pragma unroll
@@ -303,32 +308,28 @@ __global__ __launch_bounds__(kHcaThreads) __attribute__((amdgpu_waves_per_eu(2, 
           for (int v = 0; v < 16; v++) o[db][v] *= corr;
       }
       const float m_use = m_run == -INFINITY ? 0.f : m_run;    // nothing seen yet: every term below becomes 0
+      // Per 32-key tile: probabilities (vector ALU), then O^T += V^T P^T in two 16-key steps (matrix cores);
+      // step (kt, h) uses the lane's own values v = 8h .. 8h+7 of tile kt, i.e. keys kt*32 + 16h + 8*(e/4) + 4g
+      // + e%4, and V^T supplies the same keys per dim.  The tiles are independent, so the second tile's
+      // vector arithmetic can run while the first tile's matrix instructions execute.
       float ls = 0.f;
 #pragma unroll
       for (int kt = 0; kt < kKeyTiles; kt++) {
         float p[16];
+        uint32_t pk[8];                                       // probabilities, two bf16 per word
 #pragma unroll
         for (int v = 0; v < 16; v++) { p[v] = __builtin_amdgcn_exp2f(fmaf(s[kt][v], c2, -m_use)); ls += p[v]; }
 #pragma unroll
-        for (int e = 0; e < 8; e++) pk[kt][e] = pack_bf16x2(p[2 * e], p[2 * e + 1]);
+        for (int e = 0; e < 8; e++) pk[e] = pack_bf16x2(p[2 * e], p[2 * e + 1]);
+#pragma unroll
+        for (int h = 0; h < 2; h++) {
+          const u32x4_t pf = {pk[4 * h], pk[4 * h + 1], pk[4 * h + 2], pk[4 * h + 3]};
+#pragma unroll
+          for (int db = 0; db < DB; db++) o[db] = mfma16(vread(vt_lds, 2 * kt + h, db), pf, o[db]);
+        }
       }
       ls += __shfl_xor(ls, 32, 64);
       l_run += ls;
-    }
-    if (blk + 1 < nb) {
-      stage(cur ^ 1);                                         // every wavefront left that buffer at the last barrier
-      if (blk + 2 < nb) prefetch(blk + 2);
-    }
-    if (act) {
-      // O^T += V^T P^T in 16-key steps; step (kt, h) uses the lane's own values v = 8h .. 8h+7 of tile kt,
-      // i.e. keys kt*32 + 16h + 8*(e/4) + 4g + e%4, and V^T supplies the same keys per dim.
-#pragma unroll
-      for (int st = 0; st < 2 * kKeyTiles; st++) {
-        const int kt = st >> 1, h = st & 1;
-        const u32x4_t pf = {pk[kt][4 * h], pk[kt][4 * h + 1], pk[kt][4 * h + 2], pk[kt][4 * h + 3]};
-#pragma unroll
-        for (int db = 0; db < DB; db++) o[db] = mfma16(vread(vt_lds, st, db), pf, o[db]);
-      }
     }
     __syncthreads();                                          // block blk+1 staged; everyone is done with block blk
   }
