@@ -21,15 +21,26 @@ namespace {
 constexpr int kLossThreads = 256;
 constexpr int kLossWaves = kLossThreads / 64;
 
+// Orders this wavefront's LDS writes before its later LDS reads of other lanes' data.  The LDS executes
+// one wavefront's operations in issue order, so only the compiler has to be kept from reordering them.
+__device__ __forceinline__ void wave_lds_order() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
 // scratch per (position, slice): 5 floats of statistics, then K (target logit, token, draft logit) triples
 __host__ __device__ inline size_t slice_floats(int k) { return 8 + 3 * (size_t)k; }
 
 __global__ __launch_bounds__(kLossThreads) void loss_slice_kernel(const float *zq, const float *zp, int ldz, int vocab, int k,
                                                                    int n_slices, float *scratch) {
   constexpr int PER = kTopkSlice / kLossThreads;   // 16
-  __shared__ float shv[16];
+  static_assert(kLossWaves == 4, "the reductions below combine four wavefronts");
+  __shared__ float red_max[kLossWaves][2], red_sum[kLossWaves][4];
   __shared__ float cq[kLossWaves * kLossMaxK], cp[kLossWaves * kLossMaxK];
   __shared__ __attribute__((aligned(16))) uint64_t keys[kLossWaves * kLossMaxK + 2];
+  __shared__ __attribute__((aligned(16))) uint64_t ckey[kLossWaves][64];   // filtered candidates, one per lane
+  __shared__ float cqv[kLossWaves][64], cpv[kLossWaves][64];
   const int slice = blockIdx.x, rowi = blockIdx.y, t = threadIdx.x, lane = t & 63, wave = t >> 6;
   const int c0 = slice * kTopkSlice;
   const float *rq = zq + (size_t)rowi * ldz, *rp = zp + (size_t)rowi * ldz;
@@ -40,11 +51,17 @@ __global__ __launch_bounds__(kLossThreads) void loss_slice_kernel(const float *z
     vq[e] = c < vocab ? rq[c] : -INFINITY;
     vp[e] = c < vocab ? rp[c] : -INFINITY;
   }
+  // two workgroup-wide reductions, each over several quantities at once (wavefront results in LDS, then every
+  // thread combines the four wavefronts in the same fixed order)
   float mq = vq[0], mp = vp[0];
 #pragma unroll
   for (int e = 1; e < PER; e++) { mq = fmaxf(mq, vq[e]); mp = fmaxf(mp, vp[e]); }
-  mq = block_max(mq, shv);
-  mp = block_max(mp, shv);
+  mq = wave_max(mq);
+  mp = wave_max(mp);
+  if (lane == 0) { red_max[wave][0] = mq; red_max[wave][1] = mp; }
+  __syncthreads();
+  mq = fmaxf(fmaxf(red_max[0][0], red_max[1][0]), fmaxf(red_max[2][0], red_max[3][0]));
+  mp = fmaxf(fmaxf(red_max[0][1], red_max[1][1]), fmaxf(red_max[2][1], red_max[3][1]));
   float sq = 0.f, sp = 0.f, cross = 0.f;
 #pragma unroll
   for (int e = 0; e < PER; e++) {
@@ -54,13 +71,58 @@ __global__ __launch_bounds__(kLossThreads) void loss_slice_kernel(const float *z
     sp += expf(vp[e] - mp);
     cross += in ? wq * vp[e] : 0.f;
   }
-  sq = block_sum(sq, shv);
-  sp = block_sum(sp, shv);
-  cross = block_sum(cross, shv);
+  sq = wave_sum(sq);
+  sp = wave_sum(sp);
+  cross = wave_sum(cross);
+  if (lane == 0) { red_sum[wave][0] = sq; red_sum[wave][1] = sp; red_sum[wave][2] = cross; }
+  __syncthreads();
+  sq = ((red_sum[0][0] + red_sum[1][0]) + red_sum[2][0]) + red_sum[3][0];
+  sp = ((red_sum[0][1] + red_sum[1][1]) + red_sum[2][1]) + red_sum[3][1];
+  cross = ((red_sum[0][2] + red_sum[1][2]) + red_sum[2][2]) + red_sum[3][2];
   float *out = scratch + ((size_t)rowi * n_slices + slice) * slice_floats(k);
   if (t == 0) { out[0] = mq; out[1] = sq; out[2] = mp; out[3] = sp; out[4] = cross; }
 
-  // each wavefront: its k best target logits by k rounds of a wave-wide argmax over register-resident values
+  // Each wavefront finds the k best of its 1024 register-resident target logits and leaves them, best
+  // first, in keys / cq / cp [wave * k ...].
+  //
+  // Filter first (k <= 64): tau = the k-th largest of the 64 LANE maxima.  At least k values are >= tau, so
+  // every member of the wavefront's top k is >= tau; the values that pass are few (about k for scattered
+  // data) and are compacted to one per lane, then ranked against each other.  If more than 64 pass (many
+  // equal values), or k > 64, the general path below takes over: k rounds of a wave-wide argmax over all
+  // 16 values of every lane.
+  bool done = false;
+  if (k <= 64) {
+    float cur = vq[0];
+#pragma unroll
+    for (int e = 1; e < PER; e++) cur = fmaxf(cur, vq[e]);
+    float tau = -INFINITY;
+    for (int r = 0; r < k; r++) {                            // remove the largest lane maximum k times
+      tau = wave_max_dpp(cur);
+      const uint64_t holders = __ballot(cur == tau);
+      if (lane == __ffsll((long long)holders) - 1) cur = -INFINITY;   // one lane per round (lowest), ties stay for later rounds
+    }
+    ckey[wave][lane] = 0ull;
+    wave_lds_order();
+    int n_pass = 0;
+#pragma unroll
+    for (int e = 0; e < PER; e++) {
+      const int c = c0 + t + e * kLossThreads;
+      const bool pass = c < vocab && vq[e] >= tau;
+      const uint64_t mask = __ballot(pass);
+      const int pos = n_pass + __popcll(mask & ((1ull << lane) - 1ull));
+      if (pass && pos < 64) { ckey[wave][pos] = order_key(vq[e], c); cqv[wave][pos] = vq[e]; cpv[wave][pos] = vp[e]; }
+      n_pass += __popcll(mask);
+    }
+    if (n_pass <= 64) {
+      for (int r = lane; r < k; r += 64) { keys[wave * k + r] = 0ull; cq[wave * k + r] = -INFINITY; cp[wave * k + r] = 0.f; }
+      wave_lds_order();
+      const uint64_t mine = ckey[wave][lane];
+      const int rank = key_rank(ckey[wave], 64, mine, lane);
+      if (mine != 0ull && rank < k) { keys[wave * k + rank] = mine; cq[wave * k + rank] = cqv[wave][lane]; cp[wave * k + rank] = cpv[wave][lane]; }
+      done = true;
+    }
+  }
+  if (!done) {
   uint32_t taken = 0;
   for (int r = 0; r < k; r++) {
     float mv = -INFINITY;
@@ -84,6 +146,7 @@ __global__ __launch_bounds__(kLossThreads) void loss_slice_kernel(const float *z
       for (int e = 0; e < PER; e++) pv = e == e_own ? vp[e] : pv;
       cp[wave * k + r] = pv;
     }
+  }
   }
   if (t < 2) keys[kLossWaves * k + t] = 0ull;                // padding for the pairwise reads
   __syncthreads();

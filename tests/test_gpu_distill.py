@@ -106,6 +106,20 @@ def test_exact_ties_take_the_lower_token_id(env):
         check(got_topk, got_ce, want, want, want_ce)          # no alternative: the tie is exact on both sides
 
 
+def test_all_equal_target_logits(env):
+    # a zero target feature gives the same logit for every token: Omega-hat is then tokens 0 .. K-1 (lower id first),
+    # and far more than 64 values tie at the top of every wavefront (the selection's general path)
+    torch, P = env
+    ft, fd, w = wl.make_distill_inputs(26, 6, 128, 9000, "fp32")
+    ft[1] = 0.0
+    ft[4] = 0.0
+    for k in (3, 10, 70):
+        got_topk, got_ce, _ = run_gpu(torch, P, ft, fd, w, k, "fp32")
+        want, alt, want_ce = oracle_losses(ft, fd, w, k)
+        assert distill.topk_set(np.zeros(9000), k).tolist() == list(range(k))
+        check(got_topk, got_ce, want, want if k < 9000 else alt, want_ce)
+
+
 def test_topk_loss_full_size_sampled_rows(env):
     # the benchmark's launch: 4096 positions (batch 2 x 2048), LLaMA2-7B widths; the oracle takes 24 sampled rows
     torch, P = env
