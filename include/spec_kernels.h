@@ -53,6 +53,35 @@ int spec_k_attention(int32_t dtype, const void *q, const void *kcache, const voi
 int spec_k_topk_logprob(const float *logits, int32_t rows, int32_t vocab, int32_t k, float *scratch_f, int32_t *scratch_i,
                         int32_t *top_tok, float *top_lp, void *stream);
 
+/* Acceptance with SAMPLED draft tokens: the ratio rule of speculative sampling
+ * (Sec. 2, third step: "a modified rejection sampling schema"; the rule of the
+ * chain and static-tree comparison systems of Sec. 4.1).  The tree has n_nodes
+ * <= 128 nodes, node 0 the root, parents before children (tree_tok, tree_par:
+ * device int32 arrays).  p_logits[i], q_logits[i] (fp32, [n_nodes, vocab]) are
+ * the target's and the draft's logits AT node i; they score node i's children,
+ * which must have been drawn from softmax(q_logits[i] / temperature) without
+ * replacement and are tried in node order.  A child with token x is accepted
+ * with probability min(1, p(x) / q(x)); a rejection replaces p by
+ * normalise(max(p - q, 0)) and removes x from q; when all children of the
+ * current node are rejected (or it has none, or 15 tokens are accepted) the
+ * next token is drawn from the current p.  Random numbers: the library's
+ * counter-based generator, stream (seed, cycle, node).
+ * work: vocab floats of device scratch.  result: 33 device int32:
+ * [0] = m accepted nodes, [1 + d] = accepted node of depth d (d = 0 is the
+ * root), [17 + d] = token of depth d+1 for d < m and the next token at d = m. */
+int spec_k_accept_qratio(const float *p_logits, const float *q_logits, int32_t n_nodes, int32_t vocab, float temperature,
+                         const int32_t *tree_tok, const int32_t *tree_par, uint64_t seed, uint32_t cycle, float *work,
+                         int32_t *result, void *stream);
+
+/* The drafting side of the same rule: m (<= 16) distinct tokens drawn from
+ * softmax(logits / temperature) without replacement, in draw order, as the m
+ * largest of logits / temperature + Gumbel noise of stream (seed, cycle,
+ * node_stream).  logits: fp32 [vocab]; out: m device int32.  Use a node_stream
+ * that the acceptance does not use for the same cycle (the oracle uses
+ * 65536 + node). */
+int spec_k_sample_children(const float *logits, int32_t vocab, float temperature, int32_t m, uint64_t seed, uint32_t cycle,
+                           uint32_t node_stream, int32_t *out, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -85,6 +85,10 @@ lib.spec_k_attention.argtypes = [C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, 
                                  C.c_int32, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p]
 lib.spec_k_topk_logprob.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
                                     C.c_void_p, C.c_void_p]
+lib.spec_k_accept_qratio.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_float, C.c_void_p, C.c_void_p, C.c_uint64,
+                                     C.c_uint32, C.c_void_p, C.c_void_p, C.c_void_p]
+lib.spec_k_sample_children.argtypes = [C.c_void_p, C.c_int32, C.c_float, C.c_int32, C.c_uint64, C.c_uint32, C.c_uint32, C.c_void_p,
+                                       C.c_void_p]
 lib.spec_hca_attention.argtypes = [C.c_int32, C.c_void_p, C.POINTER(C.c_void_p), C.POINTER(C.c_void_p), C.c_int32, C.c_int32,
                                    C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
 lib.spec_topk_loss_scratch_bytes.restype = C.c_uint64
@@ -286,6 +290,36 @@ def spec_k_topk_logprob(logits, k: int):
     if rc:
         raise SpecError(rc, "spec_k_topk_logprob")
     return tok[:, :k], lp[:, :k]
+
+
+def spec_k_accept_qratio(p_logits, q_logits, tree_tok, tree_par, temperature: float, seed: int, cycle: int):
+    """p_logits, q_logits: fp32 torch [n_nodes, vocab]; tree_tok, tree_par: int32 torch [n_nodes].
+    Returns (accepted nodes, tokens): tokens = the accepted tokens followed by the next token."""
+    import torch
+    n, vocab = p_logits.shape
+    assert q_logits.shape == p_logits.shape and p_logits.dtype == torch.float32 and q_logits.dtype == torch.float32
+    assert p_logits.is_contiguous() and q_logits.is_contiguous()
+    work = torch.empty(vocab, dtype=torch.float32, device=p_logits.device)
+    res = torch.zeros(33, dtype=torch.int32, device=p_logits.device)
+    rc = lib.spec_k_accept_qratio(p_logits.data_ptr(), q_logits.data_ptr(), n, vocab, temperature, tree_tok.data_ptr(),
+                                  tree_par.data_ptr(), seed, cycle, work.data_ptr(), res.data_ptr(), _stream_ptr())
+    if rc:
+        raise SpecError(rc, "spec_k_accept_qratio")
+    r = res.cpu().numpy()
+    m = int(r[0])
+    return [int(x) for x in r[2:2 + m]], [int(x) for x in r[17:18 + m]]
+
+
+def spec_k_sample_children(logits, temperature: float, m: int, seed: int, cycle: int, node_stream: int):
+    """logits: fp32 torch [vocab].  Returns the m sampled tokens in draw order."""
+    import torch
+    assert logits.dtype == torch.float32 and logits.dim() == 1 and logits.is_contiguous()
+    out = torch.zeros(m, dtype=torch.int32, device=logits.device)
+    rc = lib.spec_k_sample_children(logits.data_ptr(), logits.shape[0], temperature, m, seed, cycle, node_stream, out.data_ptr(),
+                                    _stream_ptr())
+    if rc:
+        raise SpecError(rc, "spec_k_sample_children")
+    return [int(x) for x in out.cpu().numpy()]
 
 
 def spec_hca_attention(q, ks: Sequence, vs: Sequence, out=None):

@@ -864,6 +864,24 @@ int spec_k_topk_logprob(const float *logits, int32_t rows, int32_t vocab, int32_
              ? SPEC_OK : SPEC_EHIP;
 }
 
+int spec_k_accept_qratio(const float *p_logits, const float *q_logits, int32_t n_nodes, int32_t vocab, float temperature,
+                         const int32_t *tree_tok, const int32_t *tree_par, uint64_t seed, uint32_t cycle, float *work,
+                         int32_t *result, void *stream) {
+  static_assert(sizeof(AcceptResult) == 33 * sizeof(int32_t), "result layout documented in spec_kernels.h");
+  if (!p_logits || !q_logits || !tree_tok || !tree_par || !work || !result || n_nodes < 1 || n_nodes > kMaxNodes || vocab < 1 ||
+      !(temperature > 0.f))
+    return SPEC_EINVAL;
+  return launch_accept_qratio(p_logits, q_logits, vocab, temperature, tree_tok, tree_par, n_nodes, seed, cycle, work,
+                              (AcceptResult *)result, (hipStream_t)stream) == hipSuccess ? SPEC_OK : SPEC_EHIP;
+}
+
+int spec_k_sample_children(const float *logits, int32_t vocab, float temperature, int32_t m, uint64_t seed, uint32_t cycle,
+                           uint32_t node_stream, int32_t *out, void *stream) {
+  if (!logits || !out || vocab < 1 || m < 1 || m > kMaxTopK || m > vocab || !(temperature > 0.f)) return SPEC_EINVAL;
+  return launch_sample_children(logits, vocab, temperature, m, seed, cycle, node_stream, out, (hipStream_t)stream) == hipSuccess
+             ? SPEC_OK : SPEC_EHIP;
+}
+
 }  // extern "C"
 
 // ---- training-side entry points (spec_train.h) -----------------------------------------------

@@ -475,11 +475,15 @@ static hipError_t init_t() {
                              2 * 4 * 32 * kSlabStride);
 }
 hipError_t gemm_init() {
-  static bool done = false;
-  if (done) return hipSuccess;
-  hipError_t e = init_t<bf16_t>();
+  // kernel attributes belong to the device's copy of the code: once per device, for the current device
+  static bool done[64] = {};
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev >= 0 && dev < 64 && done[dev]) return hipSuccess;
+  e = init_t<bf16_t>();
   if (e == hipSuccess) e = init_t<float>();
-  done = e == hipSuccess;
+  if (dev >= 0 && dev < 64) done[dev] = e == hipSuccess;
   return e;
 }
 

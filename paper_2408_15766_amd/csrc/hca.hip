@@ -350,12 +350,14 @@ __global__ __launch_bounds__(kHcaThreads) __attribute__((amdgpu_waves_per_eu(2, 
 
 template <int HD>
 hipError_t launch_hd(const HcaArgs &a, hipStream_t st) {
-  static bool attr_done = false;
-  if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute((const void *)hca_attention_kernel<HD>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       HcaLds<HD>::total);
+  static bool attr_done[64] = {};                             // per device: the attribute belongs to the device's copy of the code
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= 64 || !attr_done[dev]) {
+    e = hipFuncSetAttribute((const void *)hca_attention_kernel<HD>, hipFuncAttributeMaxDynamicSharedMemorySize, HcaLds<HD>::total);
     if (e != hipSuccess) return e;
-    attr_done = true;
+    if (dev >= 0 && dev < 64) attr_done[dev] = true;
   }
   const int G = a.hq / a.hkv;
   const int n_qt = (a.seq + kHcaRows - 1) / kHcaRows;

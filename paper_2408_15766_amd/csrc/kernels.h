@@ -159,6 +159,14 @@ hipError_t launch_accept_greedy(const float *amax_val, const int *amax_idx, int 
 hipError_t launch_accept_sample(const float *logits, int vocab, const float2 *stat_part, float temp, const int *tree_tok,
                                 const int *tree_par, int n_nodes, uint64_t seed, uint32_t cycle, AcceptResult *res,
                                 hipStream_t st);
+// The ratio rule for sampled children: p_logits[i], q_logits[i] are the target / draft logit rows AT node i (fp32,
+// row stride vocab); children are tried in node order; work: vocab floats of scratch.
+hipError_t launch_accept_qratio(const float *p_logits, const float *q_logits, int vocab, float temp, const int *tree_tok,
+                                const int *tree_par, int n_nodes, uint64_t seed, uint32_t cycle, float *work, AcceptResult *res,
+                                hipStream_t st);
+// m <= kMaxTopK tokens drawn without replacement from softmax(logits / temp), in draw order (Gumbel-top-m).
+hipError_t launch_sample_children(const float *logits, int vocab, float temp, int m, uint64_t seed, uint32_t cycle, uint32_t node,
+                                  int *out, hipStream_t st);
 // Sample one token from softmax(logits / temp) by Gumbel-max with stream (seed, cycle, node).
 hipError_t launch_sample_row(const float *logits, int vocab, float temp, uint64_t seed, uint32_t cycle, uint32_t node,
                              int *out, hipStream_t st);

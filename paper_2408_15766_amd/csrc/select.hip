@@ -492,6 +492,134 @@ hipError_t launch_accept_sample(const float *logits, int vocab, const float2 *st
   return hipGetLastError();
 }
 
+// The ratio rule for SAMPLED children (the textbook speculative-sampling acceptance, Sec. 2 third step): at
+// node `cur` with target distribution p and draft distribution q (both softmax(row / temp)), the children,
+// drawn from q without replacement and tried in node order, are accepted with probability min(1, p_j / q_j);
+// a rejection replaces p by normalise(max(p - q, 0)) and removes the child from q; when every child is
+// rejected the next token is drawn from the current p (Gumbel-max).  One workgroup.  The current p lives in
+// `work` (vocab floats, unnormalised, with its normaliser in a register); a thread only ever re-reads the
+// entries it wrote itself, and the entry of a child's token is handed to the others through LDS.
+__global__ __launch_bounds__(kAcceptThreads) void accept_qratio_kernel(const float *p_logits, const float *q_logits, int vocab,
+                                                                       float temp, const int *tree_tok, const int *tree_par,
+                                                                       int n_nodes, uint64_t seed, uint32_t cycle, float *work,
+                                                                       AcceptResult *res) {
+  __shared__ float shv[16];
+  __shared__ int shi[16];
+  __shared__ int rem[kMaxNodes];
+  __shared__ int kid[kMaxNodes];
+  __shared__ int sh_nkid;
+  __shared__ float sh_px, sh_q0;
+  const int t = threadIdx.x;
+  int cur = 0, m = 0;
+  if (t == 0) res->node[0] = 0;
+  for (int step = 0; step <= kMaxDepth; step++) {
+    const uint64_t stream = rng_stream(seed, cycle, (uint32_t)cur);
+    const float *prow = p_logits + (size_t)cur * vocab, *qrow = q_logits + (size_t)cur * vocab;
+    float mp = -INFINITY, mq = -INFINITY;
+    for (int v = t; v < vocab; v += kAcceptThreads) { mp = fmaxf(mp, prow[v] / temp); mq = fmaxf(mq, qrow[v] / temp); }
+    mp = block_max(mp, shv);
+    mq = block_max(mq, shv);
+    float sp = 0.f, sq = 0.f;
+    for (int v = t; v < vocab; v += kAcceptThreads) {
+      const float e = expf(prow[v] / temp - mp);
+      work[v] = e;                                            // p, unnormalised: p(v) = work[v] * inv_zp
+      sp += e;
+      sq += expf(qrow[v] / temp - mq);
+    }
+    sp = block_sum(sp, shv);
+    sq = block_sum(sq, shv);
+    float inv_zp = 1.f / sp;
+    float removed = 0.f, inv_zq = 1.f;                        // q_j(v) = q(v) * inv_zq for v not removed, else 0
+    if (t == 0) {
+      int nk = 0;
+      if (m < kMaxDepth)
+        for (int c = cur + 1; c < n_nodes; c++)
+          if (tree_par[c] == cur) kid[nk++] = c;              // node order = draw order
+      sh_nkid = nk;
+    }
+    __syncthreads();
+    const int n_kid = sh_nkid;
+    int next = -1, n_rem = 0;
+    for (int ord = 0; ord < n_kid && next < 0; ord++) {
+      const int c = kid[ord];
+      const int x = tree_tok[c];
+      bool dup = false;
+      for (int r = 0; r < n_rem; r++) dup |= rem[r] == x;
+      if (x % kAcceptThreads == t) { sh_px = work[x] * inv_zp; sh_q0 = expf(qrow[x] / temp - mq) / sq; }
+      __syncthreads();
+      const float px = sh_px, q0 = dup ? 0.f : sh_q0;
+      const float u = rng_uniform(stream, (uint64_t)ord);
+      if (u * (q0 * inv_zq) < px) { next = c; break; }
+      // rejected: p <- max(p - q_j, 0), renormalised; q_{j+1} <- q_j without x
+      float part = 0.f;
+      for (int v = t; v < vocab; v += kAcceptThreads) {
+        bool gone = false;
+        for (int r = 0; r < n_rem; r++) gone |= rem[r] == v;
+        const float qv = gone ? 0.f : expf(qrow[v] / temp - mq) / sq * inv_zq;
+        const float nv = fmaxf(work[v] * inv_zp - qv, 0.f);
+        work[v] = nv;
+        part += nv;
+      }
+      const float zp = block_sum(part, shv);                  // (its barriers also order the LDS traffic of this round)
+      if (!(zp > 0.f)) { next = c; break; }                   // nothing left in the residual: c was certain
+      inv_zp = 1.f / zp;
+      if (!dup) {
+        if (t == 0) rem[n_rem] = x;
+        n_rem++;
+        removed += q0;
+        inv_zq = 1.f - removed > 0.f ? 1.f / (1.f - removed) : 0.f;
+      }
+      __syncthreads();
+    }
+    if (next >= 0) {
+      if (t == 0) { res->token[m] = tree_tok[next]; res->node[m + 1] = next; }
+      cur = next; m++;
+      __syncthreads();
+      continue;
+    }
+    ValIdx b{-INFINITY, INT_MAX};
+    for (int v = t; v < vocab; v += kAcceptThreads) {
+      const float pv = work[v] * inv_zp;
+      if (!(pv > 0.f)) continue;
+      const float z = logf(pv) + rng_gumbel(stream, v);
+      if (z > b.v || b.i == INT_MAX) { b.v = z; b.i = v; }
+    }
+    const int bonus = block_best(b, shv, shi).i;
+    if (t == 0) res->token[m] = bonus;
+    break;
+  }
+  if (t == 0) res->n_acc = m;
+}
+hipError_t launch_accept_qratio(const float *p_logits, const float *q_logits, int vocab, float temp, const int *tree_tok,
+                                const int *tree_par, int n_nodes, uint64_t seed, uint32_t cycle, float *work, AcceptResult *res,
+                                hipStream_t st) {
+  if (n_nodes < 1 || n_nodes > kMaxNodes || vocab < 1 || !(temp > 0.f)) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(accept_qratio_kernel, dim3(1), dim3(kAcceptThreads), 0, st, p_logits, q_logits, vocab, temp, tree_tok, tree_par,
+                     n_nodes, seed, cycle, work, res);
+  return hipGetLastError();
+}
+
+// out[i] = the i-th of m tokens drawn without replacement from softmax(logits / temp): the m largest of
+// logits / temp + Gumbel noise of stream (seed, cycle, node).  One workgroup, m rounds of a workgroup-wide argmax.
+__global__ __launch_bounds__(kAcceptThreads) void sample_children_kernel(const float *logits, int vocab, float temp, int m,
+                                                                         uint64_t seed, uint32_t cycle, uint32_t node, int *out) {
+  __shared__ float shv[16];
+  __shared__ int shi[16];
+  __shared__ int rem[kMaxTopK];
+  const uint64_t stream = rng_stream(seed, cycle, node);
+  for (int r = 0; r < m; r++) {
+    const int tok = gumbel_argmax(logits, vocab, temp, stream, rem, r, shv, shi);
+    if (threadIdx.x == 0) { rem[r] = tok; out[r] = tok; }
+    __syncthreads();
+  }
+}
+hipError_t launch_sample_children(const float *logits, int vocab, float temp, int m, uint64_t seed, uint32_t cycle, uint32_t node,
+                                  int *out, hipStream_t st) {
+  if (vocab < 1 || m < 1 || m > kMaxTopK || m > vocab || !(temp > 0.f)) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(sample_children_kernel, dim3(1), dim3(kAcceptThreads), 0, st, logits, vocab, temp, m, seed, cycle, node, out);
+  return hipGetLastError();
+}
+
 __global__ __launch_bounds__(kAcceptThreads) void sample_row_kernel(const float *logits, int vocab, float temp, uint64_t seed,
                                                                     uint32_t cycle, uint32_t node, int *out) {
   __shared__ float shv[16];
