@@ -78,9 +78,10 @@ int spec_k_accept_qratio(const float *p_logits, const float *q_logits, int32_t n
  * largest of logits / temperature + Gumbel noise of stream (seed, cycle,
  * node_stream).  logits: fp32 [vocab]; out: m device int32.  Use a node_stream
  * that the acceptance does not use for the same cycle (the oracle uses
- * 65536 + node). */
+ * 65536 + node).  scratch_f: vocab + 16*n_slices*18 + 32 floats, scratch_i:
+ * 16*n_slices*16 + 16 ints of device memory, n_slices = ceil(vocab / 4096). */
 int spec_k_sample_children(const float *logits, int32_t vocab, float temperature, int32_t m, uint64_t seed, uint32_t cycle,
-                           uint32_t node_stream, int32_t *out, void *stream);
+                           uint32_t node_stream, float *scratch_f, int32_t *scratch_i, int32_t *out, void *stream);
 
 #ifdef __cplusplus
 }

@@ -88,7 +88,7 @@ lib.spec_k_topk_logprob.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32,
 lib.spec_k_accept_qratio.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_float, C.c_void_p, C.c_void_p, C.c_uint64,
                                      C.c_uint32, C.c_void_p, C.c_void_p, C.c_void_p]
 lib.spec_k_sample_children.argtypes = [C.c_void_p, C.c_int32, C.c_float, C.c_int32, C.c_uint64, C.c_uint32, C.c_uint32, C.c_void_p,
-                                       C.c_void_p]
+                                       C.c_void_p, C.c_void_p, C.c_void_p]
 lib.spec_hca_attention.argtypes = [C.c_int32, C.c_void_p, C.POINTER(C.c_void_p), C.POINTER(C.c_void_p), C.c_int32, C.c_int32,
                                    C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
 lib.spec_topk_loss_scratch_bytes.restype = C.c_uint64
@@ -315,8 +315,12 @@ def spec_k_sample_children(logits, temperature: float, m: int, seed: int, cycle:
     import torch
     assert logits.dtype == torch.float32 and logits.dim() == 1 and logits.is_contiguous()
     out = torch.zeros(m, dtype=torch.int32, device=logits.device)
-    rc = lib.spec_k_sample_children(logits.data_ptr(), logits.shape[0], temperature, m, seed, cycle, node_stream, out.data_ptr(),
-                                    _stream_ptr())
+    vocab = logits.shape[0]
+    ns = (vocab + 4095) // 4096
+    sf = torch.empty(vocab + 16 * ns * 18 + 32, dtype=torch.float32, device=logits.device)
+    si = torch.empty(16 * ns * 16 + 16, dtype=torch.int32, device=logits.device)
+    rc = lib.spec_k_sample_children(logits.data_ptr(), vocab, temperature, m, seed, cycle, node_stream, sf.data_ptr(), si.data_ptr(),
+                                    out.data_ptr(), _stream_ptr())
     if rc:
         raise SpecError(rc, "spec_k_sample_children")
     return [int(x) for x in out.cpu().numpy()]

@@ -876,10 +876,17 @@ int spec_k_accept_qratio(const float *p_logits, const float *q_logits, int32_t n
 }
 
 int spec_k_sample_children(const float *logits, int32_t vocab, float temperature, int32_t m, uint64_t seed, uint32_t cycle,
-                           uint32_t node_stream, int32_t *out, void *stream) {
-  if (!logits || !out || vocab < 1 || m < 1 || m > kMaxTopK || m > vocab || !(temperature > 0.f)) return SPEC_EINVAL;
-  return launch_sample_children(logits, vocab, temperature, m, seed, cycle, node_stream, out, (hipStream_t)stream) == hipSuccess
-             ? SPEC_OK : SPEC_EHIP;
+                           uint32_t node_stream, float *scratch_f, int32_t *scratch_i, int32_t *out, void *stream) {
+  if (!logits || !out || !scratch_f || !scratch_i || vocab < 1 || m < 1 || m > kMaxTopK || m > vocab || !(temperature > 0.f))
+    return SPEC_EINVAL;
+  const int n_slices = (vocab + kTopkSlice - 1) / kTopkSlice;
+  float *z = scratch_f;                                       // [vocab], then the top-k scratch of one row (as spec_k_topk_logprob)
+  float *sc_val = z + (size_t)(vocab + 3) / 4 * 4;
+  float2 *sc_stat = (float2 *)(sc_val + (size_t)kMaxTopK * n_slices * kMaxTopK);
+  float *top_lp = (float *)(sc_stat + (size_t)kMaxTopK * n_slices);
+  int *sc_idx = scratch_i, *top_tok = scratch_i + (size_t)kMaxTopK * n_slices * kMaxTopK;
+  return launch_sample_children(logits, vocab, temperature, m, seed, cycle, node_stream, z, sc_val, sc_idx, sc_stat, top_tok, top_lp,
+                                out, (hipStream_t)stream) == hipSuccess ? SPEC_OK : SPEC_EHIP;
 }
 
 }  // extern "C"

@@ -165,8 +165,10 @@ hipError_t launch_accept_qratio(const float *p_logits, const float *q_logits, in
                                 const int *tree_par, int n_nodes, uint64_t seed, uint32_t cycle, float *work, AcceptResult *res,
                                 hipStream_t st);
 // m <= kMaxTopK tokens drawn without replacement from softmax(logits / temp), in draw order (Gumbel-top-m).
+// z: vocab floats; sc_val / sc_idx / sc_stat / top_tok / top_lp: the scratch of launch_rows_topk_logprob for one row.
 hipError_t launch_sample_children(const float *logits, int vocab, float temp, int m, uint64_t seed, uint32_t cycle, uint32_t node,
-                                  int *out, hipStream_t st);
+                                  float *z, float *sc_val, int *sc_idx, float2 *sc_stat, int *top_tok, float *top_lp, int *out,
+                                  hipStream_t st);
 // Sample one token from softmax(logits / temp) by Gumbel-max with stream (seed, cycle, node).
 hipError_t launch_sample_row(const float *logits, int vocab, float temp, uint64_t seed, uint32_t cycle, uint32_t node,
                              int *out, hipStream_t st);

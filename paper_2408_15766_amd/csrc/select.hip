@@ -600,23 +600,29 @@ hipError_t launch_accept_qratio(const float *p_logits, const float *q_logits, in
 }
 
 // out[i] = the i-th of m tokens drawn without replacement from softmax(logits / temp): the m largest of
-// logits / temp + Gumbel noise of stream (seed, cycle, node).  One workgroup, m rounds of a workgroup-wide argmax.
-__global__ __launch_bounds__(kAcceptThreads) void sample_children_kernel(const float *logits, int vocab, float temp, int m,
-                                                                         uint64_t seed, uint32_t cycle, uint32_t node, int *out) {
-  __shared__ float shv[16];
-  __shared__ int shi[16];
-  __shared__ int rem[kMaxTopK];
+// logits / temp + Gumbel noise of stream (seed, cycle, node), found by the two-stage top-k above on the
+// perturbed row (written to `z`, vocab floats).
+__global__ __launch_bounds__(kSelThreads) void perturb_gumbel_kernel(const float *logits, int vocab, float temp, uint64_t seed,
+                                                                     uint32_t cycle, uint32_t node, float *z) {
   const uint64_t stream = rng_stream(seed, cycle, node);
-  for (int r = 0; r < m; r++) {
-    const int tok = gumbel_argmax(logits, vocab, temp, stream, rem, r, shv, shi);
-    if (threadIdx.x == 0) { rem[r] = tok; out[r] = tok; }
-    __syncthreads();
-  }
+  for (int v = blockIdx.x * kSelThreads + threadIdx.x; v < vocab; v += gridDim.x * kSelThreads)
+    z[v] = logits[v] / temp + rng_gumbel(stream, v);
+}
+__global__ void copy_ints_kernel(const int *src, int n, int *dst) {
+  if ((int)threadIdx.x < n) dst[threadIdx.x] = src[threadIdx.x];
 }
 hipError_t launch_sample_children(const float *logits, int vocab, float temp, int m, uint64_t seed, uint32_t cycle, uint32_t node,
-                                  int *out, hipStream_t st) {
+                                  float *z, float *sc_val, int *sc_idx, float2 *sc_stat, int *top_tok, float *top_lp, int *out,
+                                  hipStream_t st) {
   if (vocab < 1 || m < 1 || m > kMaxTopK || m > vocab || !(temp > 0.f)) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(sample_children_kernel, dim3(1), dim3(kAcceptThreads), 0, st, logits, vocab, temp, m, seed, cycle, node, out);
+  const int blocks = (vocab + kSelThreads - 1) / kSelThreads;
+  hipLaunchKernelGGL(perturb_gumbel_kernel, dim3(blocks > 1024 ? 1024 : blocks), dim3(kSelThreads), 0, st, logits, vocab, temp, seed,
+                     cycle, node, z);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  e = launch_rows_topk_logprob(z, 1, vocab, m, sc_val, sc_idx, sc_stat, top_tok, top_lp, st);
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(copy_ints_kernel, dim3(1), dim3(64), 0, st, top_tok, m, out);
   return hipGetLastError();
 }
 
