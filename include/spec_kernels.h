@@ -1,6 +1,7 @@
 /*
  * libspec, kernel-level entry points: the individual gfx950 kernels of the
- * decode path, callable on caller-provided DEVICE buffers.  They exist so that
+ * decode path (and the acceptance rule for sampled draft tokens, which the
+ * decode loop of spec.h does not use), callable on caller-provided DEVICE buffers.  They exist so that
  * each kernel can be checked against the CPU oracle and timed in isolation;
  * the decode loop itself goes through spec.h.  All calls enqueue on `stream`
  * (a hipStream_t, NULL = default stream) and return without waiting.  dtype is
