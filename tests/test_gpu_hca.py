@@ -51,6 +51,10 @@ CASES = [
     (8, 1, 200, 2, 2, 128),       # the most streams the entry point takes
     (3, 1, 1, 1, 1, 128),         # a single position
     (2, 3, 129, 6, 3, 128),       # kv groups not a multiple of 8, one query in the last tile
+    (3, 1, 700, 4, 4, 128),       # six tiles, ragged tail
+    (2, 2, 513, 8, 2, 64),        # head dim 64, one query in the last tile
+    (8, 1, 600, 2, 1, 64),        # the widest band over several tiles
+    (1, 1, 1000, 2, 2, 128),      # plain causal, longer
 ]
 
 
