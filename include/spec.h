@@ -178,6 +178,35 @@ int64_t spec_get_kv(spec_ctx *ctx, int32_t which, int32_t layer, int32_t n_rows,
  * paths run the same kernels on the same data and give identical results. */
 int spec_set_graphs(spec_ctx *ctx, int32_t enable);
 
+/* Static draft trees (the tree of the comparison systems of Sec. 4.1: EAGLE's
+ * fixed shape, or a chain = conventional speculative sampling, Sec. 2) instead
+ * of the dynamic tree of the configuration.  The shape has n_nodes <=
+ * cfg.tree_total nodes, node 0 the root, nodes in order of depth, parents
+ * before children (HOST arrays parent[], rank[] of n_nodes ints, parent[0] =
+ * -1).  rank[i] says which of its parent's proposals node i is: the rank-th
+ * best token of the draft distribution at the parent, or, with sampled != 0
+ * (needs cfg.temperature > 0), the rank-th of the tokens DRAWN from it without
+ * replacement.  The children of a node must be listed in increasing rank; a
+ * depth may have at most 16 nodes with children; the nodes with children
+ * (root excluded) may not exceed cfg.tree_depth * cfg.tree_topk (the draft
+ * scratch the workspace was sized for).  spec_draft_tree then drafts this shape
+ * (one draft forward per depth over the nodes that have children; scores are
+ * cumulative log-probabilities for deterministic children and 0 for sampled
+ * ones) and spec_accept uses, for sampled children, the ratio rule min(1, p/q)
+ * with residual max(p - q, 0) against the draft rows kept while drafting: the
+ * tree must then be passed to spec_verify / spec_accept as drafted.  With
+ * deterministic children the acceptance is the one of the dynamic tree.
+ * buffer: spec_static_tree_bytes(...) bytes of DEVICE memory, 256-byte aligned,
+ * owned by the caller and borrowed until the context is destroyed or another
+ * shape is set (0 from spec_static_tree_bytes = shape not accepted).  Call it
+ * between cycles (after spec_create / spec_prefill / spec_accept); n_nodes = 0
+ * returns to the dynamic tree.  The static path launches its kernels
+ * individually (no graph replay).  Errors: SPEC_EINVAL (malformed shape, small
+ * buffer), SPEC_ECAP (shape beyond the configured capacity), SPEC_ESTATE. */
+uint64_t spec_static_tree_bytes(const spec_config *cfg, int32_t n_nodes, const int32_t *parent, const int32_t *rank, int32_t sampled);
+int spec_set_static_tree(spec_ctx *ctx, int32_t n_nodes, const int32_t *parent, const int32_t *rank, int32_t sampled, void *buffer,
+                         uint64_t buffer_bytes);
+
 /* Per-phase and per-kernel-class GPU time accounting with HIP events on the
  * context's stream.  level 0: off; 1: one event pair per call (draft, verify,
  * accept); 2: additionally one pair around every weight-streaming GEMM launch

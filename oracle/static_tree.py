@@ -38,10 +38,10 @@ class StaticShape:
             assert 0 <= self.parent[i] < i and 0 <= self.rank[i] < 16
             self.depth[i] = self.depth[self.parent[i]] + 1
             assert self.depth[i] >= self.depth[i - 1] and self.depth[i] <= 15, "nodes in order of depth, depth <= 15"
-        seen = set()
+        last = {}
         for i in range(1, n):
-            assert (self.parent[i], self.rank[i]) not in seen, "two children of a node with the same rank"
-            seen.add((self.parent[i], self.rank[i]))
+            assert self.rank[i] > last.get(self.parent[i], -1), "the children of a node are listed in increasing rank"
+            last[self.parent[i]] = self.rank[i]
         self.n_nodes = n
         self.children = [[i for i in range(1, n) if self.parent[i] == u] for u in range(n)]
         self.expanded = [u for u in range(n) if self.children[u]]           # nodes run through the draft model
@@ -118,14 +118,16 @@ def spec_decode_static(w, shape, prompt: np.ndarray, gen: int, shape_: StaticSha
         st.cycle += 1
         tree, q_logits = draft_static(st, shape_, temperature, sampled, seed)
         logits, feats = verify_tree(st, tree)
+        margin = np.inf
         if temperature > 0 and sampled:
-            acc, bonus, _ = qratio.accept_qratio(tree.token, tree.parent, logits, q_logits, temperature, seed, st.cycle)
+            acc, bonus, margin = qratio.accept_qratio(tree.token, tree.parent, logits, q_logits, temperature, seed, st.cycle)
         elif temperature > 0:
             acc, bonus = accept_sample(tree, logits, temperature, seed, st.cycle)
         else:
             acc, bonus = accept_greedy(tree, logits)
         if record is not None:
-            record.append(dict(n=st.n, tree=tree, logits=logits, feats=feats, q_logits=q_logits, accepted=list(acc), bonus=bonus))
+            record.append(dict(n=st.n, tree=tree, logits=logits, feats=feats, q_logits=q_logits, accepted=list(acc), bonus=bonus,
+                               margin=margin))
         emitted = commit(st, tree, feats, acc, bonus)
         out += emitted
         taus.append(len(emitted))

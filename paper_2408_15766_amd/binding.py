@@ -74,6 +74,9 @@ lib.spec_get_kv.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, _f32p, 
 lib.spec_set_profile.argtypes = [C.c_void_p, C.c_int32]
 lib.spec_set_graphs.argtypes = [C.c_void_p, C.c_int32]
 lib.spec_get_profile.argtypes = [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_int64)]
+lib.spec_static_tree_bytes.restype = C.c_uint64
+lib.spec_static_tree_bytes.argtypes = [C.POINTER(spec_config), C.c_int32, _i32p, _i32p, C.c_int32]
+lib.spec_set_static_tree.argtypes = [C.c_void_p, C.c_int32, _i32p, _i32p, C.c_int32, C.c_void_p, C.c_uint64]
 lib.spec_last_error.restype = C.c_char_p
 lib.spec_last_error.argtypes = [C.c_void_p]
 lib.spec_packed_bytes.restype = C.c_uint64
@@ -448,6 +451,22 @@ class Engine:
             self.close()
         except Exception:
             pass
+
+    def set_static_tree(self, parent, rank, sampled: bool = False) -> None:
+        """Draft a fixed tree shape from now on (see spec_set_static_tree); parent = [] returns to the dynamic tree."""
+        import torch
+        par = np.ascontiguousarray(parent, dtype=np.int32)
+        rk = np.ascontiguousarray(rank, dtype=np.int32)
+        n = int(par.shape[0])
+        if n == 0:
+            _check(self.ctx, lib.spec_set_static_tree(self.ctx, 0, None, None, 0, None, 0))
+            self._static_buffer = None
+            return
+        pp, rp = par.ctypes.data_as(_i32p), rk.ctypes.data_as(_i32p)
+        nbytes = int(lib.spec_static_tree_bytes(C.byref(self.cfg), n, pp, rp, int(sampled)))
+        buf = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=self.workspace.device)
+        _check(self.ctx, lib.spec_set_static_tree(self.ctx, n, pp, rp, int(sampled), buf.data_ptr(), nbytes))
+        self._static_buffer = buf                       # borrowed by the library
 
     # one-to-one with the C ABI
     def prefill(self, prompt) -> int:

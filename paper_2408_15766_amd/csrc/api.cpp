@@ -21,6 +21,7 @@ namespace {
 enum State { CREATED = 0, READY = 1, DRAFTED = 2, VERIFIED = 3 };
 
 constexpr int kPrefillChunk = 512;     // prompt rows per target forward during prefill
+constexpr int kDraftNodeStream = 1 << 16;  // random stream of node i's child sampling: (cycle, kDraftNodeStream + i)
 constexpr int kMaxGemmEvents = 2048;  // event pairs kept per cycle at profile level 2
 
 struct GemmPlan { int n_split; };
@@ -80,6 +81,17 @@ struct spec_ctx {
   AcceptResult *acc = nullptr;
   HostStage *stage = nullptr;
   size_t part_floats = 0;
+
+  // static tree shape (spec_set_static_tree); n_nodes == 0: the dynamic tree of the configuration
+  struct StaticHost {
+    int n_nodes = 0, max_depth = 0, n_expanded = 0;       // n_expanded: nodes of depth >= 1 that have children
+    bool sampled = false;
+    int rows[kMaxDepth + 1] = {};                         // expanded nodes per depth (depth 0: the root, 1 if it has children)
+    int width[kMaxDepth + 1] = {};                        // proposals needed per node of that depth (max over its nodes)
+  } st;
+  StaticTables st_tb{};
+  int *st_qrow_of = nullptr, *st_enode = nullptr;         // device: node -> row of st_qrows; (depth, row) -> node
+  float *st_qrows = nullptr;                              // device: draft logit rows of the expanded nodes (sampled children)
 
   // HIP graph of the verify forward (replayed every cycle; needs a non-default stream)
   bool graphs = true;
@@ -415,6 +427,70 @@ int sync(spec_ctx *c) {
   return SPEC_OK;
 }
 
+// End of a drafting call: the device tree goes to the host arrays of the caller.
+int finish_draft(spec_ctx *c, spec_tree *out) {
+  c->gemm_bucket = 0;
+  HIPCHK(c, hipMemcpyAsync(&c->stage->tree_n, c->t_n, offsetof(HostStage, pos), hipMemcpyDeviceToHost, c->stream));
+  phase_end(c, 0);
+  int rc = sync(c);
+  if (rc) return rc;
+  const HostStage &s = *c->stage;
+  out->n_nodes = s.tree_n;
+  for (int j = 0; j < s.tree_n; j++) {
+    out->token[j] = s.tok[j]; out->parent[j] = s.par[j]; out->depth[j] = s.dep[j];
+    if (out->score) out->score[j] = s.sc[j];
+  }
+  c->state = DRAFTED;
+  return SPEC_OK;
+}
+
+// Proposals of the rows just run through the LM head (c->dlogits, `rows` rows, the nodes of depth `depth`):
+// the `width` best tokens per row, or `width` tokens drawn without replacement when children are sampled
+// (the rows' logits are then kept for the acceptance).
+int static_proposals(spec_ctx *c, int rows, int depth, int width, int first_qrow) {
+  const spec_config &g = c->cfg;
+  const float *src = c->dlogits;
+  if (c->st.sampled) {
+    HIPCHK(c, hipMemcpyAsync(c->st_qrows + (size_t)first_qrow * g.vocab, c->dlogits, (size_t)rows * g.vocab * 4, hipMemcpyDeviceToDevice,
+                             c->stream));
+    HIPCHK(c, launch_perturb_rows(c->dlogits, rows, g.vocab, g.temperature, g.seed, c->cycle, c->st_enode + depth * kMaxTopK, c->logits,
+                                  c->stream));
+    src = c->logits;                                          // free until the verify forward writes it
+  }
+  HIPCHK(c, launch_rows_topk_logprob(src, rows, g.vocab, width, c->sc_val, c->sc_idx, c->sc_stat, c->top_tok, c->top_lp, c->stream));
+  return SPEC_OK;
+}
+
+// Drafting of a static tree shape; the root step's draft forward has run (m1 pending rows, c->dlogits row 0 =
+// the draft's logits at the root).  One draft forward per depth over the nodes that have children.
+int draft_static(spec_ctx *c, int m1) {
+  const spec_ctx::StaticHost &st = c->st;
+  const int with_scores = st.sampled ? 0 : 1;
+  int qrow = 0;
+  if (st.rows[0] > 0) {
+    int rc = static_proposals(c, 1, 0, st.width[0], qrow);
+    if (rc) return rc;
+    qrow += 1;
+  }
+  HIPCHK(c, launch_static_step(c->st_tb, 1, c->top_tok, c->top_lp, m1 - 1, c->root_tok, c->t_base, with_scores, c->ds, c->t_n, c->t_tok,
+                               c->t_par, c->t_dep, c->t_sc, c->stream));
+  for (int d = 1; d < st.max_depth; d++) {
+    const int rows = st.rows[d];
+    if (rows == 0) break;                                     // no node of this depth has children: nothing deeper exists
+    RowTables fr{c->ds.front_tok, c->ds.front_pos, c->ds.front_slot, c->ds.front_depth, c->ds.front_anc};
+    int rc = draft_forward(c, rows, c->n, c->gfeat, c->ds.front_src, fr, c->n + d - 1);
+    if (rc) return rc;
+    rc = lm_head(c, c->gfeat, rows, c->dlogits);
+    if (rc) return rc;
+    rc = static_proposals(c, rows, d, st.width[d], qrow);
+    if (rc) return rc;
+    qrow += rows;
+    HIPCHK(c, launch_static_step(c->st_tb, d + 1, c->top_tok, c->top_lp, m1 - 1, c->root_tok, c->t_base, with_scores, c->ds, c->t_n,
+                                 c->t_tok, c->t_par, c->t_dep, c->t_sc, c->stream));
+  }
+  return SPEC_OK;
+}
+
 }  // namespace
 
 // =============================================================================================
@@ -571,6 +647,11 @@ int spec_draft_tree(spec_ctx *c, spec_tree *out) {
   if (rc) return rc;
   rc = lm_head(c, (const char *)c->gfeat + (size_t)(m1 - 1) * d * c->esz, 1, c->dlogits);
   if (rc) return rc;
+  if (c->st.n_nodes > 0) {
+    rc = draft_static(c, m1);
+    if (rc) return rc;
+    return finish_draft(c, out);
+  }
   HIPCHK(c, launch_rows_topk_logprob(c->dlogits, 1, g.vocab, K, c->sc_val, c->sc_idx, c->sc_stat, c->top_tok, c->top_lp, c->stream));
   HIPCHK(c, launch_pool_init(c->ds, c->top_tok, c->top_lp, K, m1 - 1, c->t_base, c->stream));
   // expansion steps 2..D (the frontier's k nodes, each fed (parent's predicted feature, own token)) and
@@ -607,19 +688,7 @@ int spec_draft_tree(spec_ctx *c, spec_tree *out) {
     rc = expand_all(nullptr, c->n, 0);
     if (rc) return rc;
   }
-  c->gemm_bucket = 0;
-  HIPCHK(c, hipMemcpyAsync(&c->stage->tree_n, c->t_n, offsetof(HostStage, pos), hipMemcpyDeviceToHost, c->stream));
-  phase_end(c, 0);
-  rc = sync(c);
-  if (rc) return rc;
-  const HostStage &s = *c->stage;
-  out->n_nodes = s.tree_n;
-  for (int j = 0; j < s.tree_n; j++) {
-    out->token[j] = s.tok[j]; out->parent[j] = s.par[j]; out->depth[j] = s.dep[j];
-    if (out->score) out->score[j] = s.sc[j];
-  }
-  c->state = DRAFTED;
-  return SPEC_OK;
+  return finish_draft(c, out);
 }
 
 int spec_verify(spec_ctx *c, const spec_tree *tree) {
@@ -703,7 +772,11 @@ int spec_accept(spec_ctx *c, const spec_tree *tree, int32_t *out_tokens, int32_t
   const int N = c->last_nodes;
   HIPCHK(c, hipSetDevice(g.device));
   phase_begin(c, 2);
-  if (g.temperature > 0.f) {
+  if (g.temperature > 0.f && c->st.n_nodes > 0 && c->st.sampled) {
+    // sampled children: the ratio rule against the draft rows kept while drafting (c->part serves as its scratch)
+    HIPCHK(c, launch_accept_qratio(c->logits, c->st_qrows, c->st_qrow_of, g.vocab, g.temperature, c->t_tok, c->t_par, N, g.seed, c->cycle,
+                                   c->part, c->acc, c->stream));
+  } else if (g.temperature > 0.f) {
     HIPCHK(c, launch_rows_softmax_stats(c->logits, N, g.vocab, g.temperature, c->stats, c->stream));
     HIPCHK(c, launch_accept_sample(c->logits, g.vocab, c->stats, g.temperature, c->t_tok, c->t_par, N, g.seed, c->cycle, c->acc, c->stream));
   } else {
@@ -784,6 +857,101 @@ int64_t spec_get_kv(spec_ctx *c, int32_t which, int32_t layer, int32_t n_rows, f
   int64_t r = copy_widen(c, k, n, k_dst);
   if (r < 0) return r;
   return copy_widen(c, v, n, v_dst);
+}
+
+namespace {
+struct StaticPlan {                   // host-side analysis of a static shape
+  int depth[kMaxNodes], erow[kMaxNodes], eoff[kMaxNodes], qrow_of[kMaxNodes], enode[(kMaxDepth + 1) * kMaxTopK];
+  spec_ctx::StaticHost h;
+};
+// Validates a shape and derives its tables; returns nullptr or the reason it is not accepted.
+const char *plan_static(int n, const int32_t *parent, const int32_t *rank, StaticPlan *p) {
+  if (n < 1 || n > kMaxNodes || !parent || !rank) return "n_nodes outside 1..128 or NULL arrays";
+  if (parent[0] != -1) return "node 0 must be the root (parent -1)";
+  int kids[kMaxNodes] = {}, last_rank[kMaxNodes];
+  for (int i = 0; i < n; i++) { last_rank[i] = -1; p->erow[i] = p->eoff[i] = p->qrow_of[i] = -1; }
+  for (int i = 0; i < (kMaxDepth + 1) * kMaxTopK; i++) p->enode[i] = 0;
+  p->depth[0] = 0;
+  p->h = spec_ctx::StaticHost{};
+  for (int i = 1; i < n; i++) {
+    const int u = parent[i];
+    if (u < 0 || u >= i) return "a parent must precede its children";
+    p->depth[i] = p->depth[u] + 1;
+    if (p->depth[i] < p->depth[i - 1]) return "nodes must be in order of depth";
+    if (p->depth[i] > kMaxDepth) return "deeper than 15";
+    if (rank[i] < 0 || rank[i] >= kMaxTopK) return "rank outside 0..15";
+    if (rank[i] <= last_rank[u]) return "the children of a node must be listed in increasing rank";
+    last_rank[u] = rank[i];
+    kids[u]++;
+    p->h.width[p->depth[u]] = std::max(p->h.width[p->depth[u]], rank[i] + 1);
+    p->h.max_depth = std::max(p->h.max_depth, p->depth[i]);
+  }
+  int qrow = 0, off = 0;
+  for (int i = 0; i < n; i++) {
+    if (!kids[i]) continue;
+    const int d = p->depth[i];
+    if (p->h.rows[d] >= kMaxTopK) return "more than 16 nodes with children at one depth";
+    p->erow[i] = p->h.rows[d];
+    p->enode[d * kMaxTopK + p->h.rows[d]] = kDraftNodeStream + i;
+    p->h.rows[d]++;
+    p->qrow_of[i] = qrow++;
+    if (i > 0) { p->eoff[i] = off++; p->h.n_expanded++; }
+  }
+  for (int d = 1; d < p->h.max_depth; d++)
+    if (p->h.rows[d] == 0) return "a depth without expanded nodes below a deeper node";   // cannot happen for a tree; defensive
+  p->h.n_nodes = n;
+  return nullptr;
+}
+size_t static_table_ints() { return (size_t)6 * kMaxNodes + (kMaxDepth + 1) * kMaxTopK; }
+}  // namespace
+
+uint64_t spec_static_tree_bytes(const spec_config *cfg, int32_t n_nodes, const int32_t *parent, const int32_t *rank, int32_t sampled) {
+  StaticPlan p;
+  if (!cfg || plan_static(n_nodes, parent, rank, &p) != nullptr) return 0;
+  size_t bytes = align_up(static_table_ints() * 4);
+  if (sampled) bytes += align_up((size_t)(p.h.n_expanded + (p.h.rows[0] ? 1 : 0)) * cfg->vocab * 4);
+  return bytes;
+}
+
+int spec_set_static_tree(spec_ctx *c, int32_t n_nodes, const int32_t *parent, const int32_t *rank, int32_t sampled, void *buffer,
+                         uint64_t buffer_bytes) {
+  if (!c) return SPEC_EINVAL;
+  if (c->state != CREATED && c->state != READY) return fail(c, SPEC_ESTATE, "set_static_tree: a drafted tree is pending");
+  if (n_nodes == 0) { c->st = spec_ctx::StaticHost{}; return SPEC_OK; }          // back to the dynamic tree
+  const spec_config &g = c->cfg;
+  StaticPlan p;
+  const char *why = plan_static(n_nodes, parent, rank, &p);
+  if (why) return fail(c, SPEC_EINVAL, "set_static_tree: %s", why);
+  if (n_nodes > g.tree_total) return fail(c, SPEC_ECAP, "set_static_tree: %d nodes exceed the configured tree_total %d", n_nodes, g.tree_total);
+  if (p.h.n_expanded > g.tree_depth * g.tree_topk)
+    return fail(c, SPEC_ECAP, "set_static_tree: %d expanded nodes exceed the draft scratch of tree_depth * tree_topk = %d", p.h.n_expanded,
+                g.tree_depth * g.tree_topk);
+  if (sampled && !(g.temperature > 0.f)) return fail(c, SPEC_EINVAL, "set_static_tree: sampled children need temperature > 0");
+  if (sampled && (c->part_floats < (size_t)g.vocab || n_nodes > g.tree_total))
+    return fail(c, SPEC_ECAP, "set_static_tree: workspace too small for the ratio rule's scratch");
+  const uint64_t need = spec_static_tree_bytes(&g, n_nodes, parent, rank, sampled);
+  if (!buffer || ((uintptr_t)buffer & 255) || buffer_bytes < need)
+    return fail(c, SPEC_EINVAL, "set_static_tree: buffer NULL, not 256-byte aligned or smaller than %llu bytes", (unsigned long long)need);
+  HIPCHK(c, hipSetDevice(g.device));
+  std::vector<int> host(static_table_ints(), 0);
+  int *hp = host.data();
+  int *h_parent = hp, *h_rank = hp + kMaxNodes, *h_depth = hp + 2 * kMaxNodes, *h_erow = hp + 3 * kMaxNodes, *h_eoff = hp + 4 * kMaxNodes,
+      *h_qrow = hp + 5 * kMaxNodes, *h_enode = hp + 6 * kMaxNodes;
+  for (int i = 0; i < n_nodes; i++) {
+    h_parent[i] = parent[i]; h_rank[i] = rank[i]; h_depth[i] = p.depth[i]; h_erow[i] = p.erow[i]; h_eoff[i] = p.eoff[i]; h_qrow[i] = p.qrow_of[i];
+  }
+  memcpy(h_enode, p.enode, sizeof(p.enode));
+  HIPCHK(c, hipStreamSynchronize(c->stream));
+  HIPCHK(c, hipMemcpy(buffer, host.data(), host.size() * 4, hipMemcpyHostToDevice));
+  int *dp = (int *)buffer;
+  c->st_tb.n_nodes = n_nodes;
+  c->st_tb.parent = dp; c->st_tb.rank = dp + kMaxNodes; c->st_tb.depth = dp + 2 * kMaxNodes;
+  c->st_tb.erow = dp + 3 * kMaxNodes; c->st_tb.eoff = dp + 4 * kMaxNodes;
+  c->st_qrow_of = dp + 5 * kMaxNodes; c->st_enode = dp + 6 * kMaxNodes;
+  c->st_qrows = sampled ? (float *)((char *)buffer + align_up(static_table_ints() * 4)) : nullptr;
+  c->st = p.h;
+  c->st.sampled = sampled != 0;
+  return SPEC_OK;
 }
 
 int spec_set_graphs(spec_ctx *c, int32_t enable) {
@@ -871,7 +1039,7 @@ int spec_k_accept_qratio(const float *p_logits, const float *q_logits, int32_t n
   if (!p_logits || !q_logits || !tree_tok || !tree_par || !work || !result || n_nodes < 1 || n_nodes > kMaxNodes || vocab < 1 ||
       !(temperature > 0.f))
     return SPEC_EINVAL;
-  return launch_accept_qratio(p_logits, q_logits, vocab, temperature, tree_tok, tree_par, n_nodes, seed, cycle, work,
+  return launch_accept_qratio(p_logits, q_logits, nullptr, vocab, temperature, tree_tok, tree_par, n_nodes, seed, cycle, work,
                               (AcceptResult *)result, (hipStream_t)stream) == hipSuccess ? SPEC_OK : SPEC_EHIP;
 }
 

@@ -161,9 +161,25 @@ hipError_t launch_accept_sample(const float *logits, int vocab, const float2 *st
                                 hipStream_t st);
 // The ratio rule for sampled children: p_logits[i], q_logits[i] are the target / draft logit rows AT node i (fp32,
 // row stride vocab); children are tried in node order; work: vocab floats of scratch.
-hipError_t launch_accept_qratio(const float *p_logits, const float *q_logits, int vocab, float temp, const int *tree_tok,
-                                const int *tree_par, int n_nodes, uint64_t seed, uint32_t cycle, float *work, AcceptResult *res,
-                                hipStream_t st);
+// qrow_of (nullable): node -> row of q_logits holding the draft's logits at that node (-1: the node has no children).
+hipError_t launch_accept_qratio(const float *p_logits, const float *q_logits, const int *qrow_of, int vocab, float temp,
+                                const int *tree_tok, const int *tree_par, int n_nodes, uint64_t seed, uint32_t cycle, float *work,
+                                AcceptResult *res, hipStream_t st);
+
+// A static tree shape on the device (node 0 = root, nodes in order of depth, parents before children).
+struct StaticTables {
+  int n_nodes;
+  const int *parent, *rank, *depth;     // [n_nodes]; rank = which of the parent's proposals the node is
+  const int *erow;                      // [n_nodes] row of the node in its depth's draft forward, -1 if it has no children
+  const int *eoff;                      // [n_nodes] draft scratch slot offset of such a node (depth >= 1), -1 otherwise
+};
+// Fills the tree arrays of the nodes of depth d from the proposals of depth d-1 and prepares the next forward's rows.
+hipError_t launch_static_step(const StaticTables &tb, int d, const int *top_tok, const float *top_lp, int root_row,
+                              const int *root_tok, const int *n_draft, int with_scores, const DraftState &s, int *t_n, int *t_tok,
+                              int *t_par, int *t_dep, float *t_sc, hipStream_t st);
+// z[r] = logits[r] / temp + Gumbel noise of stream (seed, cycle, node_stream[r]); rows <= kMaxTopK.
+hipError_t launch_perturb_rows(const float *logits, int rows, int vocab, float temp, uint64_t seed, uint32_t cycle,
+                               const int *node_stream, float *z, hipStream_t st);
 // m <= kMaxTopK tokens drawn without replacement from softmax(logits / temp), in draw order (Gumbel-top-m).
 // z: vocab floats; sc_val / sc_idx / sc_stat / top_tok / top_lp: the scratch of launch_rows_topk_logprob for one row.
 hipError_t launch_sample_children(const float *logits, int vocab, float temp, int m, uint64_t seed, uint32_t cycle, uint32_t node,

@@ -499,9 +499,10 @@ hipError_t launch_accept_sample(const float *logits, int vocab, const float2 *st
 // rejected the next token is drawn from the current p (Gumbel-max).  One workgroup.  The current p lives in
 // `work` (vocab floats, unnormalised, with its normaliser in a register); a thread only ever re-reads the
 // entries it wrote itself, and the entry of a child's token is handed to the others through LDS.
-__global__ __launch_bounds__(kAcceptThreads) void accept_qratio_kernel(const float *p_logits, const float *q_logits, int vocab,
-                                                                       float temp, const int *tree_tok, const int *tree_par,
-                                                                       int n_nodes, uint64_t seed, uint32_t cycle, float *work,
+__global__ __launch_bounds__(kAcceptThreads) void accept_qratio_kernel(const float *p_logits, const float *q_logits,
+                                                                       const int *qrow_of, int vocab, float temp,
+                                                                       const int *tree_tok, const int *tree_par, int n_nodes,
+                                                                       uint64_t seed, uint32_t cycle, float *work,
                                                                        AcceptResult *res) {
   __shared__ float shv[16];
   __shared__ int shi[16];
@@ -514,7 +515,18 @@ __global__ __launch_bounds__(kAcceptThreads) void accept_qratio_kernel(const flo
   if (t == 0) res->node[0] = 0;
   for (int step = 0; step <= kMaxDepth; step++) {
     const uint64_t stream = rng_stream(seed, cycle, (uint32_t)cur);
-    const float *prow = p_logits + (size_t)cur * vocab, *qrow = q_logits + (size_t)cur * vocab;
+    if (t == 0) {
+      int nk = 0;
+      if (m < kMaxDepth)
+        for (int c = cur + 1; c < n_nodes; c++)
+          if (tree_par[c] == cur) kid[nk++] = c;              // node order = draw order
+      sh_nkid = nk;
+    }
+    __syncthreads();
+    const int n_kid = sh_nkid;
+    const float *prow = p_logits + (size_t)cur * vocab;
+    // the draft row of a node without children is never read (it may not exist: qrow_of[cur] < 0)
+    const float *qrow = n_kid == 0 ? prow : q_logits + (size_t)(qrow_of ? qrow_of[cur] : cur) * vocab;
     float mp = -INFINITY, mq = -INFINITY;
     for (int v = t; v < vocab; v += kAcceptThreads) { mp = fmaxf(mp, prow[v] / temp); mq = fmaxf(mq, qrow[v] / temp); }
     mp = block_max(mp, shv);
@@ -530,15 +542,6 @@ __global__ __launch_bounds__(kAcceptThreads) void accept_qratio_kernel(const flo
     sq = block_sum(sq, shv);
     float inv_zp = 1.f / sp;
     float removed = 0.f, inv_zq = 1.f;                        // q_j(v) = q(v) * inv_zq for v not removed, else 0
-    if (t == 0) {
-      int nk = 0;
-      if (m < kMaxDepth)
-        for (int c = cur + 1; c < n_nodes; c++)
-          if (tree_par[c] == cur) kid[nk++] = c;              // node order = draw order
-      sh_nkid = nk;
-    }
-    __syncthreads();
-    const int n_kid = sh_nkid;
     int next = -1, n_rem = 0;
     for (int ord = 0; ord < n_kid && next < 0; ord++) {
       const int c = kid[ord];
@@ -590,12 +593,66 @@ __global__ __launch_bounds__(kAcceptThreads) void accept_qratio_kernel(const flo
   }
   if (t == 0) res->n_acc = m;
 }
-hipError_t launch_accept_qratio(const float *p_logits, const float *q_logits, int vocab, float temp, const int *tree_tok,
-                                const int *tree_par, int n_nodes, uint64_t seed, uint32_t cycle, float *work, AcceptResult *res,
-                                hipStream_t st) {
+hipError_t launch_accept_qratio(const float *p_logits, const float *q_logits, const int *qrow_of, int vocab, float temp,
+                                const int *tree_tok, const int *tree_par, int n_nodes, uint64_t seed, uint32_t cycle, float *work,
+                                AcceptResult *res, hipStream_t st) {
   if (n_nodes < 1 || n_nodes > kMaxNodes || vocab < 1 || !(temp > 0.f)) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(accept_qratio_kernel, dim3(1), dim3(kAcceptThreads), 0, st, p_logits, q_logits, vocab, temp, tree_tok, tree_par,
-                     n_nodes, seed, cycle, work, res);
+  hipLaunchKernelGGL(accept_qratio_kernel, dim3(1), dim3(kAcceptThreads), 0, st, p_logits, q_logits, qrow_of, vocab, temp, tree_tok,
+                     tree_par, n_nodes, seed, cycle, work, res);
+  return hipGetLastError();
+}
+
+// ---- static tree shapes ----------------------------------------------------------------------
+// After the proposals of the nodes of depth d-1 are known (top_tok / top_lp, row = the node's row in its
+// depth's forward, 0 for the root): fill token / parent / depth / score of the nodes of depth d, and for those
+// of them that have children set up their row of the next draft forward (the same tables the dynamic
+// expansion builds: token, source row of the parent's predicted feature, depth argument, ancestor slots).
+__global__ void static_step_kernel(StaticTables tb, int d, const int *top_tok, const float *top_lp, int root_row,
+                                   const int *root_tok, const int *n_draft_ptr, int with_scores, DraftState s, int *t_n,
+                                   int *t_tok, int *t_par, int *t_dep, float *t_sc) {
+  const int i = threadIdx.x;
+  const int n_draft = *n_draft_ptr;
+  if (i == 0 && d == 1) { *t_n = tb.n_nodes; t_tok[0] = *root_tok; t_par[0] = -1; t_dep[0] = 0; t_sc[0] = 0.f; }
+  if (i < 1 || i >= tb.n_nodes || tb.depth[i] != d) return;
+  const int p = tb.parent[i];
+  const int pr = d == 1 ? 0 : tb.erow[p];
+  const int tok = top_tok[pr * kMaxTopK + tb.rank[i]];
+  t_tok[i] = tok; t_par[i] = p; t_dep[i] = d;
+  t_sc[i] = with_scores ? (d == 1 ? 0.f : t_sc[p]) + top_lp[pr * kMaxTopK + tb.rank[i]] : 0.f;
+  const int r = tb.erow[i];
+  if (r < 0) return;
+  s.front_tok[r] = tok;
+  s.front_src[r] = d == 1 ? root_row : tb.erow[p];
+  s.front_depth[r] = d - 1;
+  s.front_slot[r] = n_draft + tb.eoff[i];
+  s.front_pos[r] = n_draft + d;
+  for (int a = i, q = d - 1; q >= 0; q--, a = tb.parent[a]) s.front_anc[r * kAncStride + q] = tb.eoff[a];
+}
+hipError_t launch_static_step(const StaticTables &tb, int d, const int *top_tok, const float *top_lp, int root_row,
+                              const int *root_tok, const int *n_draft, int with_scores, const DraftState &s, int *t_n, int *t_tok,
+                              int *t_par, int *t_dep, float *t_sc, hipStream_t st) {
+  if (tb.n_nodes < 1 || tb.n_nodes > kMaxNodes || d < 1 || d > kMaxDepth) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(static_step_kernel, dim3(1), dim3(kMaxNodes), 0, st, tb, d, top_tok, top_lp, root_row, root_tok, n_draft,
+                     with_scores, s, t_n, t_tok, t_par, t_dep, t_sc);
+  return hipGetLastError();
+}
+
+// z[r][v] = logits[r][v] / temp + Gumbel noise of stream (seed, cycle, node_stream[r]) for rows r < rows.
+__global__ __launch_bounds__(kSelThreads) void perturb_rows_kernel(const float *logits, int vocab, float temp, uint64_t seed,
+                                                                   uint32_t cycle, const int *node_stream, float *z) {
+  const int r = blockIdx.y;
+  const uint64_t stream = rng_stream(seed, cycle, (uint32_t)node_stream[r]);
+  const float *row = logits + (size_t)r * vocab;
+  float *zr = z + (size_t)r * vocab;
+  for (int v = blockIdx.x * kSelThreads + threadIdx.x; v < vocab; v += gridDim.x * kSelThreads)
+    zr[v] = row[v] / temp + rng_gumbel(stream, v);
+}
+hipError_t launch_perturb_rows(const float *logits, int rows, int vocab, float temp, uint64_t seed, uint32_t cycle,
+                               const int *node_stream, float *z, hipStream_t st) {
+  if (rows < 1 || rows > kMaxTopK || vocab < 1 || !(temp > 0.f)) return hipErrorInvalidValue;
+  const int blocks = (vocab + kSelThreads - 1) / kSelThreads;
+  hipLaunchKernelGGL(perturb_rows_kernel, dim3(blocks > 256 ? 256 : blocks, rows), dim3(kSelThreads), 0, st, logits, vocab, temp, seed,
+                     cycle, node_stream, z);
   return hipGetLastError();
 }
 
