@@ -172,8 +172,11 @@ int64_t spec_get_features(spec_ctx *ctx, float *dst, int64_t cap);
 int64_t spec_get_kv(spec_ctx *ctx, int32_t which, int32_t layer, int32_t n_rows, float *k_dst, float *v_dst, int64_t cap);
 
 /* The verify forward, and the draft expansion steps with the rerank, are each
- * captured once into a HIP graph and replayed every cycle (their launch arguments
- * are fixed or device-resident), which removes most of the per-kernel launch cost.  Graphs need a non-default stream; with stream == NULL
+ * captured into a HIP graph and replayed every cycle (their launch arguments
+ * are fixed or device-resident), which removes most of the per-kernel launch cost.
+ * A graph's attention launches are sized for the context rounded up to a multiple
+ * of 256 positions; it is captured again (about a millisecond) when the context
+ * outgrows that, so the cycle time does not depend on max_seq.  Graphs need a non-default stream; with stream == NULL
  * or after spec_set_graphs(ctx, 0) every kernel is launched individually.  Both
  * paths run the same kernels on the same data and give identical results. */
 int spec_set_graphs(spec_ctx *ctx, int32_t enable);

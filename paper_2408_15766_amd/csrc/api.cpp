@@ -21,6 +21,11 @@ namespace {
 enum State { CREATED = 0, READY = 1, DRAFTED = 2, VERIFIED = 3 };
 
 constexpr int kPrefillChunk = 512;     // prompt rows per target forward during prefill
+// A captured forward sizes its attention launches for a bound on the key positions, not for the positions of
+// the cycle it was captured in.  The bound is the context rounded up to the next multiple of kGraphBucket, and
+// the graph is captured again when the context outgrows it: sizing for max_seq instead costs 2-9 % of the verify
+// at a 512-token context (workgroups that find nothing to do still have to be dispatched).
+constexpr int kGraphBucket = 256;
 constexpr int kDraftNodeStream = 1 << 16;  // random stream of node i's child sampling: (cycle, kDraftNodeStream + i)
 constexpr int kMaxGemmEvents = 2048;  // event pairs kept per cycle at profile level 2
 
@@ -97,7 +102,9 @@ struct spec_ctx {
   bool graphs = true;
   hipGraphExec_t verify_exec = nullptr;
   int verify_exec_rows = 0;
+  int verify_exec_bound = 0;              // largest key position the captured launches are sized for
   hipGraphExec_t expand_exec = nullptr;   // draft expansion steps 2..D + rerank
+  int expand_exec_bound = 0;
 
   // profiling
   int prof_level = 0;
@@ -672,16 +679,20 @@ int spec_draft_tree(spec_ctx *c, spec_tree *out) {
     return SPEC_OK;
   };
   if (c->graphs && c->stream != nullptr && c->prof_level < 2) {
-    if (c->expand_exec == nullptr) {
+    const int need = c->n + D;                                  // largest key position of a draft row of this cycle
+    if (c->expand_exec == nullptr || need > c->expand_exec_bound) {
+      if (c->expand_exec) { (void)hipGraphExecDestroy(c->expand_exec); c->expand_exec = nullptr; }
+      const int bound = std::min(c->seq_draft - 1, (need / kGraphBucket + 1) * kGraphBucket - 1);
       hipGraph_t graph = nullptr;
       HIPCHK(c, hipStreamBeginCapture(c->stream, hipStreamCaptureModeThreadLocal));
-      rc = expand_all(c->t_base, 0, c->seq_draft - 1);
+      rc = expand_all(c->t_base, 0, bound);
       hipError_t e = hipStreamEndCapture(c->stream, &graph);
       if (rc) { if (graph) (void)hipGraphDestroy(graph); return rc; }
       if (e != hipSuccess) return fail(c, SPEC_EHIP, "graph capture (draft): %s", hipGetErrorString(e));
       e = hipGraphInstantiate(&c->expand_exec, graph, nullptr, nullptr, 0);
       (void)hipGraphDestroy(graph);
       if (e != hipSuccess) { c->expand_exec = nullptr; return fail(c, SPEC_EHIP, "graph instantiate (draft): %s", hipGetErrorString(e)); }
+      c->expand_exec_bound = bound;
     }
     HIPCHK(c, hipGraphLaunch(c->expand_exec, c->stream));
   } else {
@@ -728,11 +739,13 @@ int spec_verify(spec_ctx *c, const spec_tree *tree) {
   if (use_graph) {
     // Every launch argument of the forward is either fixed or read from device memory (the tree
     // tables and the base), so the sequence is captured once and replayed each cycle.
-    if (c->verify_exec == nullptr || c->verify_exec_rows != N) {
+    const int need = c->n + kMaxDepth;                          // largest key position a row of this cycle can have
+    if (c->verify_exec == nullptr || c->verify_exec_rows != N || need > c->verify_exec_bound) {
       if (c->verify_exec) { (void)hipGraphExecDestroy(c->verify_exec); c->verify_exec = nullptr; }
+      const int bound = std::min(g.max_seq - 1, (need / kGraphBucket + 1) * kGraphBucket - 1);
       hipGraph_t graph = nullptr;
       HIPCHK(c, hipStreamBeginCapture(c->stream, hipStreamCaptureModeThreadLocal));
-      rc = target_forward(c, N, 0, rt, g.max_seq - 1, c->t_base);
+      rc = target_forward(c, N, 0, rt, bound, c->t_base);
       if (!rc) rc = lm_head(c, c->feats, N, c->logits);
       hipError_t e = hipStreamEndCapture(c->stream, &graph);
       if (rc) { if (graph) (void)hipGraphDestroy(graph); return rc; }
@@ -741,6 +754,7 @@ int spec_verify(spec_ctx *c, const spec_tree *tree) {
       (void)hipGraphDestroy(graph);
       if (e != hipSuccess) { c->verify_exec = nullptr; return fail(c, SPEC_EHIP, "graph instantiate: %s", hipGetErrorString(e)); }
       c->verify_exec_rows = N;
+      c->verify_exec_bound = bound;
     }
     HIPCHK(c, hipGraphLaunch(c->verify_exec, c->stream));
   } else {
