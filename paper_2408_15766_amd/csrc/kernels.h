@@ -10,7 +10,10 @@ constexpr int kMaxDepth = 15;          // longest root-to-node path handled by t
 constexpr int kAncStride = kMaxDepth + 1;
 constexpr int kMaxTopK = 16;
 constexpr int kMaxNodes = 128;
-constexpr int kAttnPart = 128;         // key positions per attention partial (fixed absolute boundaries)
+#ifndef SPEC_ATTN_PART
+#define SPEC_ATTN_PART 128
+#endif
+constexpr int kAttnPart = SPEC_ATTN_PART;   // key positions per attention partial (fixed absolute boundaries)
 constexpr int kTopkSlice = 4096;       // vocabulary entries per first-stage top-k workgroup
 
 // ---- gemm.hip --------------------------------------------------------------------------------
