@@ -11,8 +11,8 @@
 //
 // Two code paths share one definition of the key order:
 //
-//  * vector path (attn_part_kernel): one wavefront handles (row, kv head, part of kAttnPart = 128
-//    key positions) and all G query heads that share the kv head; keys are taken 64 at a time,
+//  * vector path (attn_part_kernel): one wavefront handles (row, kv head, part of the key positions:
+//    kAttnPart = 128 of them below position kAttnNear, kAttnFarPart beyond) and all G query heads that share the kv head; keys are taken 64 at a time,
 //    lane = position offset for the scores (wave shuffles give the running max and sum of the
 //    online softmax), then lane = output dim for P*V, which runs over the value rows staged in
 //    LDS key by key in position order.  Used for fp32 storage, and for the TAIL
@@ -29,7 +29,8 @@
 //    only, so a row is computed by the same instructions over the same key groups whether it is
 //    alone or part of a tree.
 //
-// Parts (fixed absolute boundaries, kAttnPart positions) are merged per row in ascending order, the tail
+// Parts (fixed absolute boundaries: attn_part_begin; larger parts for far keys, where a long context would otherwise
+// mean many partials to merge and many short workgroups) are merged per row in ascending order, the tail
 // last, by attn_combine_kernel.  In the hybrid path the bulk and the tail are independent and run in ONE
 // launch (different workgroups), so the chain per layer is two dependent kernels.
 #include "common.h"
@@ -81,8 +82,8 @@ __device__ __forceinline__ void attn_part_body(const AttnArgs &a, int i, int hk,
   constexpr int VROW = PartLds<T>::vrow(HD);         // LDS bytes per staged value row
   const int base = a.base_ptr ? *a.base_ptr : a.base;  // device-resident when the launch is replayed from a graph
   const int p = base + a.depth[i];
-  const int k_lo = part * kAttnPart;
-  const int k_hi = min(p + 1, k_lo + kAttnPart);
+  const int k_lo = attn_part_begin(part);
+  const int k_hi = min(p + 1, attn_part_begin(part + 1));
   if (k_lo >= k_hi) return;
 
   const float *qrow = (const float *)a.q + ((size_t)i * a.hq + (size_t)hk * G) * HD;   // queries are fp32
@@ -288,7 +289,7 @@ __global__ __launch_bounds__(HD) void attn_combine_kernel(AttnArgs a) {
   __shared__ float red[2];
   const int i = blockIdx.x, h = blockIdx.y, d = threadIdx.x;
   const int p = (a.base_ptr ? *a.base_ptr : a.base) + a.depth[i];
-  const int n_front = a.tail_only ? (bulk_end(p) + kAttnPart - 1) / kAttnPart : p / kAttnPart + 1;
+  const int n_front = attn_parts_covering(a.tail_only ? bulk_end(p) : p + 1);
   const int n_parts = n_front + (a.tail_only ? 1 : 0);
   const float *src = a.part + ((size_t)i * a.hq + h) * a.max_parts * (HD + 2);
   auto slot = [&](int t) { return (size_t)(t < n_front ? t : a.max_parts - 1) * (HD + 2); };
@@ -346,7 +347,6 @@ __device__ __forceinline__ f32x16_t mfma_bf16(const u32x4_t &a, const u32x4_t &b
   return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, a), __builtin_bit_cast(bf16x8_t, b), c, 0, 0, 0);
 }
 
-constexpr int kBulkBlocksPerPart = kAttnPart / 32;
 
 // One launch covers both regions of the hybrid path.  Workgroups [0, n_bulk) (n_bulk = bulk_parts * kv heads
 // * q_groups, part fastest) run the matrix-core bulk: NW waves, wave w owns 32 "query rows" (row i, head gh
@@ -390,8 +390,8 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2, 2)))
   // keys [0, key_lim) are the union of the rows' bulk regions: all of them exist and are initialised
   const int key_lim = a.base_ptr ? min(a.bulk_keys, bulk_end(base + kMaxDepth)) : a.bulk_keys;
   const int n_blocks = (key_lim + 31) / 32;
-  const int b_lo = part * kBulkBlocksPerPart;
-  const int b_hi = min(b_lo + kBulkBlocksPerPart, n_blocks);
+  const int b_lo = attn_part_begin(part) / 32;
+  const int b_hi = min(attn_part_begin(part + 1) / 32, n_blocks);
   if (b_lo >= b_hi) return;
 
   const int r = (qgroup * NW + wave) * 32 + c;
@@ -542,7 +542,7 @@ static hipError_t launch_thg(AttnArgs a, int max_pos, hipStream_t st) {
     a.tail_only = 1;
     a.bulk_keys = bulk_end(max_pos);
     a.bulk_blocks = (a.bulk_keys + 31) / 32;
-    a.bulk_parts = (a.bulk_blocks + kBulkBlocksPerPart - 1) / kBulkBlocksPerPart;
+    a.bulk_parts = attn_parts_covering(a.bulk_keys);
     if (a.bulk_parts + 1 > a.max_parts) return hipErrorInvalidValue;
     const int qblocks = (a.rows * G + 31) / 32;
     if (qblocks <= 1) e = launch_hybrid<HD, G, 1>(a, 1, st);
@@ -552,7 +552,7 @@ static hipError_t launch_thg(AttnArgs a, int max_pos, hipStream_t st) {
   } else {
     a.tail_only = 0;
     a.bulk_blocks = 0;
-    const int n_parts = max_pos / kAttnPart + 1;
+    const int n_parts = attn_parts_covering(max_pos + 1);
     if (n_parts > a.max_parts) return hipErrorInvalidValue;
     hipLaunchKernelGGL((attn_part_kernel<T, HD, G>), dim3(a.rows, a.hkv, n_parts), dim3(64), 0, st, a);
     e = hipGetLastError();

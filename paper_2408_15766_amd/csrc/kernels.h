@@ -13,7 +13,24 @@ constexpr int kMaxNodes = 128;
 #ifndef SPEC_ATTN_PART
 #define SPEC_ATTN_PART 128
 #endif
-constexpr int kAttnPart = SPEC_ATTN_PART;   // key positions per attention partial (fixed absolute boundaries)
+constexpr int kAttnPart = SPEC_ATTN_PART;   // key positions per attention partial (fixed absolute boundaries) ...
+#ifndef SPEC_ATTN_NEAR
+#define SPEC_ATTN_NEAR 1024
+#endif
+#ifndef SPEC_ATTN_FAR_PART
+#define SPEC_ATTN_FAR_PART 256
+#endif
+constexpr int kAttnNear = SPEC_ATTN_NEAR;         // ... for key positions below this;
+constexpr int kAttnFarPart = SPEC_ATTN_FAR_PART;  // beyond it a partial covers this many positions
+static_assert(kAttnNear % kAttnPart == 0 && kAttnFarPart % 32 == 0 && kAttnPart % 32 == 0, "parts are whole 32-key blocks");
+// First key position of partial t, and the number of partials that intersect [0, keys).  The boundaries are
+// absolute (they depend on nothing but t), so a row's partition is the same in every launch.
+__host__ __device__ inline int attn_part_begin(int t) {
+  return t <= kAttnNear / kAttnPart ? t * kAttnPart : kAttnNear + (t - kAttnNear / kAttnPart) * kAttnFarPart;
+}
+__host__ __device__ inline int attn_parts_covering(int keys) {
+  return keys <= kAttnNear ? (keys + kAttnPart - 1) / kAttnPart : kAttnNear / kAttnPart + (keys - kAttnNear + kAttnFarPart - 1) / kAttnFarPart;
+}
 constexpr int kTopkSlice = 4096;       // vocabulary entries per first-stage top-k workgroup
 
 // ---- gemm.hip --------------------------------------------------------------------------------
@@ -79,7 +96,7 @@ struct AttnArgs {
   const int *depth;                     // [rows]
   const int *anc;                       // [rows][kAncStride] or nullptr
   float scale;
-  float *part;                          // scratch: [rows][hq][max_parts][hd + 2]; max_parts >= max_pos/kAttnPart + 2
+  float *part;                          // scratch: [rows][hq][max_parts][hd + 2]; max_parts >= attn_parts_covering(max_pos + 1) + 1
   int max_parts;
   void *out;
   int tail_only, bulk_keys, bulk_blocks, bulk_parts, q_groups;   // set by launch_attention (hybrid matrix-core / vector split)

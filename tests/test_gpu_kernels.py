@@ -102,6 +102,9 @@ ATTN_CASES = [
     ("bf16", 8, 2, 128, 700, 60, True),
     ("bf16", 8, 1, 128, 63, 1, True),           # a single row (plain decoding)
     ("bf16", 4, 4, 128, 192, 64, False),        # chain crossing a part boundary
+    ("fp32", 2, 1, 64, 1010, 24, True),         # rows straddle position 1024, where the parts become 256 keys long
+    ("fp32", 2, 2, 64, 1500, 8, True),          # several of the longer parts, the last one ragged (vector path)
+    ("bf16", 4, 2, 128, 1290, 40, True),        # the same on the matrix-core path
 ]
 
 
