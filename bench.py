@@ -38,6 +38,8 @@ def parse():
     ap.add_argument("--forced-accept", type=int, default=4,
                     help="draft tokens accepted per cycle in the teacher-forced extra pass (0 = skip the pass)")
     ap.add_argument("--tree", default="", help="override the draft tree as depth,topk,total (default: the config's 6,10,60)")
+    ap.add_argument("--static-tree", default="", help="draft a static shape instead of the dynamic tree: chainN (N draft tokens in a "
+                    "row) or tree26 (4/8/8/4/1 nodes per depth); add ':sampled' for sampled children (needs a T > 0 config)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-hca", action="store_true", help="skip the training-attention measurement (separate object in the JSON line)")
     ap.add_argument("--no-loss", action="store_true", help="skip the distillation-loss measurement (separate object in the JSON line)")
@@ -220,6 +222,17 @@ def topk_loss_bench(sh, with_cpu, launches=5):
     return res
 
 
+def static_shape(name):
+    """(parent, rank) arrays of a named static tree shape (see spec_set_static_tree)."""
+    if name.startswith("chain"):
+        n = int(name[5:])
+        return [-1] + list(range(n)), [0] * (n + 1)
+    if name == "tree26":
+        return ([-1, 0, 0, 0, 0, 1, 1, 1, 2, 2, 3, 3, 4, 5, 5, 5, 6, 6, 8, 8, 10, 13, 13, 14, 16, 21],
+                [0, 0, 1, 2, 3, 0, 1, 2, 0, 1, 0, 1, 0, 0, 1, 2, 0, 1, 0, 1, 0, 0, 1, 0, 0, 0])
+    raise SystemExit(f"bench.py: unknown static tree {name!r}")
+
+
 def main():
     a = parse()
     if a.gpus != 1:
@@ -252,6 +265,9 @@ def main():
 
     # ---- pass A: the timed region ------------------------------------------------------------
     eng = P.Engine(sh, weights, max_seq=max_seq)
+    static_name, _, static_mode = a.static_tree.partition(":")
+    if static_name:
+        eng.set_static_tree(*static_shape(static_name), sampled=static_mode == "sampled")
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     eng.prefill(prompt)
@@ -273,7 +289,7 @@ def main():
 
     # plain autoregressive decoding through the same kernels (tree = the root alone): the 1.00x reference
     # (only at T = 0, where the emitted tokens are a function of the weights alone)
-    forced_accept = max(0, min(sh.tree_depth, a.forced_accept)) if sh.temperature == 0 and sh.tree_total > 1 else 0
+    forced_accept = max(0, min(sh.tree_depth, a.forced_accept)) if sh.temperature == 0 and sh.tree_total > 1 and not static_name else 0
     plain_extra = (total_cycles * (forced_accept + 1) + 1 - total_cycles) if forced_accept else 0
     plain = P.Engine(sh, weights, max_seq=max_seq, tree=(1, 1, 1))
     stream = [plain.prefill(prompt)]
@@ -295,7 +311,9 @@ def main():
         "warmup": a.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": sh.dtype, "data": "synthetic",
         "config": {"workload": f"{sh.name} shape, random init N(0,0.02), prompt {sh.prompt_len} uniform tokens, "
-                               f"tree depth {sh.tree_depth} top-k {sh.tree_topk} total {sh.tree_total}, T={sh.temperature:g}, batch 1"},
+                               + (f"static tree {a.static_tree}" if static_name else
+                                  f"tree depth {sh.tree_depth} top-k {sh.tree_topk} total {sh.tree_total}")
+                               + f", T={sh.temperature:g}, batch 1"},
         "ms_per_cycle": ms_per_step,
         "mean_accepted_length": emitted / a.steps,
         "plain_decode_tokens_per_s": pe / plain_dt,
@@ -326,6 +344,8 @@ def main():
     if not a.no_roofline_pass:
         for level in (1, 2):
             eng = P.Engine(sh, weights, max_seq=max_seq)
+            if static_name:
+                eng.set_static_tree(*static_shape(static_name), sampled=static_mode == "sampled")
             eng.prefill(prompt)
             run_cycles(eng, a.warmup)
             P.spec_set_profile(eng.ctx, level)
