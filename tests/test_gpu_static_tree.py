@@ -63,6 +63,22 @@ def test_static_shapes_greedy_match_oracle(env, tiny_gpu, name):
         assert np.abs(a["logits"] - b["logits"]).max() < 1e-4
 
 
+def test_static_tree_filling_the_configured_total_uses_the_replayed_verify(env, tiny_gpu):
+    # with n_nodes == tree_total the verify forward is the captured graph (as for the dynamic tree); same results
+    torch, P = env
+    sh, hw, w64, prompt, dw = tiny_gpu
+    eng = P.Engine(sh, dw, tree=(6, 8, EAGLE_LIKE.n_nodes))
+    eng.set_static_tree(EAGLE_LIKE.parent, EAGLE_LIKE.rank)
+    rec = []
+    got, taus = eng.generate(prompt, 24, record=rec)
+    orec = []
+    want, wt = spec_decode_static(w64, sh, prompt, 24, EAGLE_LIKE, record=orec)
+    assert got == want and taus == wt
+    for a, b in zip(rec, orec):
+        assert list(a["tree"].token) == list(b["tree"].token)
+        assert np.abs(a["logits"] - b["logits"]).max() < 1e-4
+
+
 def test_static_tree_point_mass_rule_matches_oracle(env, tiny_gpu):
     torch, P = env
     sh, hw, w64, prompt, dw = tiny_gpu
