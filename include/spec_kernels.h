@@ -18,8 +18,8 @@ extern "C" {
 #endif
 
 /* Weight-streaming projection used for every matrix of the model (QKV, O,
- * gate/up, down, draft fc, LM head; target forward of Sec. 2's "evaluates ...
- * in parallel" step):   part[s][i][c] = sum over the s-th K range of
+ * gate/up, down, draft fc, LM head; the parallel scoring of all draft tokens
+ * by the target, Sec. 2, second step):   part[s][i][c] = sum over the s-th K range of
  * x[i][k] * w[c][k].  Up to three weight matrices (w0, w1, w2; rows0..2 rows
  * each, [rows, in] in the PACKED layout of spec_pack_weight; unused ones
  * NULL / 0) share x and write consecutive column ranges.  x: [m, in] with row stride ldx elements,
@@ -55,7 +55,7 @@ int spec_k_topk_logprob(const float *logits, int32_t rows, int32_t vocab, int32_
                         int32_t *top_tok, float *top_lp, void *stream);
 
 /* Acceptance with SAMPLED draft tokens: the ratio rule of speculative sampling
- * (Sec. 2, third step: "a modified rejection sampling schema"; the rule of the
+ * (Sec. 2, third step: the modified rejection sampling it names; the rule of the
  * chain and static-tree comparison systems of Sec. 4.1).  The tree has n_nodes
  * <= 128 nodes, node 0 the root, parents before children (tree_tok, tree_par:
  * device int32 arrays).  p_logits[i], q_logits[i] (fp32, [n_nodes, vocab]) are
