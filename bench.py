@@ -28,6 +28,12 @@ HBM_PEAK_GBPS = 8000.0
 MEASURED_TRAFFIC_BYTES_PER_LAUNCH = {"llama2-7b": 113.5e6}
 
 
+# Mean acceptance length the paper reports for its trained drafts (Table 1, mean over its three benchmarks), per model
+# and temperature.  Used only for a labelled projection: random-init drafts never match the target.
+PAPER_TAU = {("llama2-7b", 0): 5.15, ("llama2-7b", 1): 4.92, ("llama2-13b", 0): 5.58, ("llama2-13b", 1): 5.42,
+             ("llama3-8b", 0): 5.08, ("llama3-8b", 1): 4.80, ("llama3-70b", 0): 5.21, ("llama3-70b", 1): 5.16}
+
+
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -49,12 +55,14 @@ def parse():
     return ap.parse_args()
 
 
-def run_cycles(eng, n_cycles, out=None):
+def run_cycles(eng, n_cycles, out=None, stamps=None):
     emitted = 0
     for _ in range(n_cycles):
         t = eng.draft_tree()
         eng.verify(t)
-        toks = eng.accept(t)
+        toks = eng.accept(t)                  # returns host integers: the cycle's device work has finished here
+        if stamps is not None:
+            stamps.append(time.perf_counter())
         emitted += len(toks)
         if out is not None:
             out.extend(toks)
@@ -280,10 +288,13 @@ def main():
     gc.freeze()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    emitted = run_cycles(eng, a.steps)
+    stamps = [t0]
+    emitted = run_cycles(eng, a.steps, stamps=stamps)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     eng.close()
+    per_cycle = sorted((b - a_) * 1e3 for a_, b in zip(stamps, stamps[1:]))
+    pick = lambda f: per_cycle[min(len(per_cycle) - 1, int(f * len(per_cycle)))]
     tokens_per_s = emitted / dt
     ms_per_step = dt / a.steps * 1e3
 
@@ -315,11 +326,20 @@ def main():
                                   f"tree depth {sh.tree_depth} top-k {sh.tree_topk} total {sh.tree_total}")
                                + f", T={sh.temperature:g}, batch 1"},
         "ms_per_cycle": ms_per_step,
+        "cycle_ms_p10_median_p90": [pick(0.1), pick(0.5), pick(0.9)],
         "mean_accepted_length": emitted / a.steps,
         "plain_decode_tokens_per_s": pe / plain_dt,
         "plain_decode_ms_per_token": plain_dt / a.steps * 1e3,
         "prefill_ms": prefill_s * 1e3, "prefill_tokens_per_s": sh.prompt_len / prefill_s,
     }
+
+    tau = PAPER_TAU.get((wl.BY_NAME[a.config].name, 0 if sh.temperature == 0 else 1))
+    if tau and not (a.layers or a.tree or static_name):
+        out["projection_at_paper_tau"] = {
+            "what": "PROJECTION, not a measurement: the paper's mean acceptance length (Table 1) divided by this run's "
+                    "measured cycle time; the measured cycles themselves accept about one token",
+            "tau": tau, "tokens_per_s": tau / (ms_per_step * 1e-3),
+            "speedup_over_plain_decode_same_kernels": tau / (ms_per_step * 1e-3) / (pe / plain_dt)}
 
     # ---- teacher-forced trees: the same cycles at a paper-like acceptance length (separately labelled) ----
     if forced_accept:

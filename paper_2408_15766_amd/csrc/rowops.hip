@@ -229,7 +229,7 @@ __global__ void reduce_rope_kv_kernel(const float *part, int n_split, int m_pad,
     return;
   }
   const float2 cs = rope[i * half + j];
-  const float ra = a * cs.x - b * cs.y, rb = b * cs.x + a * cs.y;
+  const float ra = rope_first(a, b, cs), rb = rope_second(a, b, cs);
   if (head < hq) {                                     // query head: kept in fp32, it is read once and never cached
     float *dst = q + ((size_t)i * hq + head) * hd;
     dst[j] = ra;
