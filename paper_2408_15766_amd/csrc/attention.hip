@@ -33,12 +33,22 @@
 // mean many partials to merge and many short workgroups) are merged per row in ascending order, the tail
 // last, by attn_combine_kernel.  In the hybrid path the bulk and the tail are independent and run in ONE
 // launch (different workgroups), so the chain per layer is two dependent kernels.
+#include <type_traits>
+
 #include "common.h"
 #include "kernels.h"
 
 namespace spec {
 
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;
+
+template <int N, int I = 0, typename F>
+__device__ __forceinline__ void unrolled(F &&f) {
+  if constexpr (I < N) {
+    f(std::integral_constant<int, I>{});
+    unrolled<N, I + 1>(f);
+  }
+}
 
 template <typename T> struct Chunk;   // 16-byte chunk -> floats
 template <> struct Chunk<float> {
@@ -353,6 +363,10 @@ __device__ __forceinline__ f32x16_t mfma_bf16(const u32x4_t &a, const u32x4_t &b
 // of the kv group), r = (qgroup*NW + w)*32 + lane%32, i = r / G, gh = r % G.  The remaining workgroups run
 // the vector tail, one (row, kv head) item per wavefront on the first kTailWaves wavefronts, and leave it in
 // the last part slot.  The two kinds of work are independent; attn_combine_kernel merges them afterwards.
+#ifndef SPEC_ATTN_RING
+#define SPEC_ATTN_RING 1
+#endif
+constexpr int kBulkRing = SPEC_ATTN_RING;   // register sets for K/V blocks in flight per bulk workgroup
 template <int NW> struct TailWaves { static constexpr int value = NW < 4 ? NW : 4; };
 template <int HD, int G, int NW>
 __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_hybrid_kernel(AttnArgs a) {
@@ -403,8 +417,13 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2, 2)))
   const bf16_t *kg = (const bf16_t *)a.kcache + (size_t)hk * HD;
   const bf16_t *vg = (const bf16_t *)a.vcache + (size_t)hk * HD;
   constexpr int PPR = HD * 2 / 16;                           // pieces per key row
-  u32x4_t kreg[PIECES], vreg[PIECES];
-  auto prefetch = [&](int b) {
+  // The global loads of a block land in one of R register sets, so that R blocks are in flight.  Measured on
+  // MI355X, more than one set does not pay: the arithmetic of a block, not the wait for its loads, is what a
+  // workgroup spends its time on.
+  constexpr int R = kBulkRing;
+  u32x4_t kreg[R][PIECES], vreg[R][PIECES];
+  auto prefetch = [&](auto set_tag, int b) {
+    constexpr int SET = decltype(set_tag)::value;
 #pragma unroll
     for (int e = 0; e < PIECES; e++) {
       const int q = tid + e * NT;
@@ -412,23 +431,13 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2, 2)))
       // The last block may reach past key_lim; those keys are masked for every row, so they are read from
       // key key_lim - 1 instead (initialised, inside the cache; key_lim >= 1 for every block that runs).
       const size_t off = (size_t)min(b * 32 + key, key_lim - 1) * row_stride + piece * 8;
-      kreg[e] = *(const u32x4_t *)(kg + off);
-      vreg[e] = *(const u32x4_t *)(vg + off);
+      kreg[SET][e] = *(const u32x4_t *)(kg + off);
+      vreg[SET][e] = *(const u32x4_t *)(vg + off);
     }
   };
-  prefetch(b_lo);                                            // first K/V block in flight while the queries load
-  // query fragments: step kk covers dims kk*16 + g*8 .. +8
-  u32x4_t qhi[KK], qlo[KK];
-  {
-    const float *qrow = (const float *)a.q + ((size_t)i * a.hq + (size_t)hk * G + gh) * HD;
-#pragma unroll
-    for (int kk = 0; kk < KK; kk++) {
-      float x[8];
-      const float4 x0 = *(const float4 *)(qrow + kk * 16 + g * 8), x1 = *(const float4 *)(qrow + kk * 16 + g * 8 + 4);
-      x[0] = x0.x; x[1] = x0.y; x[2] = x0.z; x[3] = x0.w; x[4] = x1.x; x[5] = x1.y; x[6] = x1.z; x[7] = x1.w;
-      split8(x, qhi[kk], qlo[kk]);
-    }
-  }
+  // A wavefront whose 32 query rows all lie past the last row only helps to load and stage the blocks.
+  const bool computes = __builtin_amdgcn_readfirstlane((qgroup * NW + wave) * 32 < a.rows * G ? 1 : 0) != 0;
+  u32x4_t qhi[KK], qlo[KK];                                  // query fragments: step kk covers dims kk*16 + g*8 .. +8
   f32x16_t o[DB];
 #pragma unroll
   for (int db = 0; db < DB; db++)
@@ -436,15 +445,16 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2, 2)))
     for (int v = 0; v < 16; v++) o[db][v] = 0.f;
   float m_run = -INFINITY, l_run = 0.f;
 
-  auto stage = [&](int buf) {
+  auto stage = [&](auto set_tag, int buf) {
+    constexpr int SET = decltype(set_tag)::value;
     unsigned char *k_lds = lds + buf * kBulkBuf, *vt_lds = k_lds + 32 * KSTR;
 #pragma unroll
     for (int e = 0; e < PIECES; e++) {
       const int q = tid + e * NT;
       if (q < 32 * PPR) {
         const int key = q / PPR, piece = q % PPR;
-        *(u32x4_t *)(k_lds + key * KSTR + piece * 16) = kreg[e];
-        const uint32_t w[4] = {vreg[e].x, vreg[e].y, vreg[e].z, vreg[e].w};
+        *(u32x4_t *)(k_lds + key * KSTR + piece * 16) = kreg[SET][e];
+        const uint32_t w[4] = {vreg[SET][e].x, vreg[SET][e].y, vreg[SET][e].z, vreg[SET][e].w};
 #pragma unroll
         for (int d2 = 0; d2 < 8; d2++)                       // V^T[dim][key]
           *(uint16_t *)(vt_lds + (piece * 8 + d2) * VSTR + key * 2) = (uint16_t)(w[d2 >> 1] >> ((d2 & 1) * 16));
@@ -452,71 +462,98 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2, 2)))
     }
   };
 
-  // K/V blocks alternate between two LDS buffers: block b+1 is staged (from the registers its global loads
-  // filled during block b-1's compute) between the two matrix-core phases of block b, and the loads of
-  // block b+2 are issued right after; one barrier per block.
-  stage(0);
-  __syncthreads();
-  if (b_lo + 1 < b_hi) prefetch(b_lo + 1);
-  for (int b = b_lo; b < b_hi; b++) {
-    const int cur = (b - b_lo) & 1;
-    const unsigned char *k_lds = lds + cur * kBulkBuf, *vt_lds = k_lds + 32 * KSTR;
-
-    f32x16_t s;
+  // One part = NB blocks, b_lo .. b_lo + NB - 1, as straight-line code: every load and every wait for a load
+  // is unconditional, so the compiler counts outstanding loads exactly and a block waits for its own set only.
+  // Blocks at or past b_hi (a part cut short by the end of the keys) are loaded from clamped addresses, staged
+  // and skipped by the arithmetic.  K/V blocks alternate between two LDS buffers: block j+1 is staged between the
+  // two matrix-core phases of block j and its register set is refilled right away with block j+1+R; one barrier
+  // per block.
+  auto run = [&](auto nb_tag) {
+    constexpr int NB = decltype(nb_tag)::value;
+    static_assert(NB >= 1 && NB <= 16, "a part is unrolled block by block");
+    unrolled<(R < NB ? R : NB)>([&](auto t_tag) { prefetch(t_tag, b_lo + decltype(t_tag)::value); });
+    {
+      const float *qrow = (const float *)a.q + ((size_t)i * a.hq + (size_t)hk * G + gh) * HD;
 #pragma unroll
-    for (int v = 0; v < 16; v++) s[v] = 0.f;
-#pragma unroll
-    for (int kk = 0; kk < KK; kk++) {
-      const u32x4_t kf = *(const u32x4_t *)(k_lds + c * KSTR + kk * 32 + g * 16);
-      s = mfma_bf16(kf, qhi[kk], s);
-      s = mfma_bf16(kf, qlo[kk], s);
-    }
-    // s[v] = q . k for key 8*(v/4) + 4*g + v%4 of the block and query row c
-    // keys at or past k_end are masked: they add exact zeros, so a row's result does not depend on them
-    const int key0 = b * 32 + 4 * g;
-    float mb = -INFINITY;
-#pragma unroll
-    for (int v = 0; v < 16; v++) {
-      s[v] = key0 + 8 * (v >> 2) + (v & 3) < k_end ? s[v] * a.scale : -INFINITY;
-      mb = fmaxf(mb, s[v]);
-    }
-    mb = fmaxf(mb, __shfl_xor(mb, 32, 64));
-    const float m_new = fmaxf(m_run, mb);
-    const float corr = m_new == -INFINITY ? 1.f : __expf(m_run - m_new);
-    float pv[16], ls = 0.f;
-#pragma unroll
-    for (int v = 0; v < 16; v++) { pv[v] = s[v] == -INFINITY ? 0.f : __expf(s[v] - m_new); ls += pv[v]; }
-    ls += __shfl_xor(ls, 32, 64);
-    l_run = l_run * corr + ls;
-    m_run = m_new;
-#pragma unroll
-    for (int db = 0; db < DB; db++)
-#pragma unroll
-      for (int v = 0; v < 16; v++) o[db][v] *= corr;
-    if (b + 1 < b_hi) {
-      stage(cur ^ 1);                                        // every wave left that buffer at the last barrier
-      if (b + 2 < b_hi) prefetch(b + 2);
-    }
-    // O^T += V^T P^T over two 16-key steps; step t uses the lane's own values v = 8t .. 8t+7,
-    // i.e. keys 16t + 8*(e/4) + 4g + e%4, and V^T supplies the same keys per dim.
-#pragma unroll
-    for (int t = 0; t < 2; t++) {
-      float x[8];
-#pragma unroll
-      for (int e = 0; e < 8; e++) x[e] = pv[8 * t + e];
-      u32x4_t phi, plo;
-      split8(x, phi, plo);
-#pragma unroll
-      for (int db = 0; db < DB; db++) {
-        const unsigned char *vp = vt_lds + (db * 32 + c) * VSTR + (16 * t + 4 * g) * 2;
-        const u32x2_t v0 = *(const u32x2_t *)vp, v1 = *(const u32x2_t *)(vp + 16);
-        const u32x4_t vf = {v0.x, v0.y, v1.x, v1.y};
-        o[db] = mfma_bf16(vf, phi, o[db]);
-        o[db] = mfma_bf16(vf, plo, o[db]);
+      for (int kk = 0; kk < KK; kk++) {
+        float x[8];
+        const float4 x0 = *(const float4 *)(qrow + kk * 16 + g * 8), x1 = *(const float4 *)(qrow + kk * 16 + g * 8 + 4);
+        x[0] = x0.x; x[1] = x0.y; x[2] = x0.z; x[3] = x0.w; x[4] = x1.x; x[5] = x1.y; x[6] = x1.z; x[7] = x1.w;
+        split8(x, qhi[kk], qlo[kk]);
       }
     }
-    __syncthreads();                                         // block b+1 staged; everyone is done with block b
-  }
+    stage(std::integral_constant<int, 0>{}, 0);
+    __syncthreads();
+    if constexpr (R < NB) prefetch(std::integral_constant<int, 0>{}, b_lo + R);
+    unrolled<NB>([&](auto j_tag) {
+      constexpr int j = decltype(j_tag)::value, cur = j & 1;
+      const int b = b_lo + j;
+      const bool live = computes && b < b_hi;                // same for all lanes of a wavefront
+      const unsigned char *k_lds = lds + cur * kBulkBuf, *vt_lds = k_lds + 32 * KSTR;
+      float pv[16];
+      if (live) {
+        f32x16_t s;
+#pragma unroll
+        for (int v = 0; v < 16; v++) s[v] = 0.f;
+#pragma unroll
+        for (int kk = 0; kk < KK; kk++) {
+          const u32x4_t kf = *(const u32x4_t *)(k_lds + c * KSTR + kk * 32 + g * 16);
+          s = mfma_bf16(kf, qhi[kk], s);
+          s = mfma_bf16(kf, qlo[kk], s);
+        }
+        // s[v] = q . k for key 8*(v/4) + 4*g + v%4 of the block and query row c
+        // keys at or past k_end are masked: they add exact zeros, so a row's result does not depend on them
+        const int key0 = b * 32 + 4 * g;
+        float mb = -INFINITY;
+#pragma unroll
+        for (int v = 0; v < 16; v++) {
+          s[v] = key0 + 8 * (v >> 2) + (v & 3) < k_end ? s[v] * a.scale : -INFINITY;
+          mb = fmaxf(mb, s[v]);
+        }
+        mb = fmaxf(mb, __shfl_xor(mb, 32, 64));
+        const float m_new = fmaxf(m_run, mb);
+        const float corr = m_new == -INFINITY ? 1.f : __expf(m_run - m_new);
+        float ls = 0.f;
+#pragma unroll
+        for (int v = 0; v < 16; v++) { pv[v] = s[v] == -INFINITY ? 0.f : __expf(s[v] - m_new); ls += pv[v]; }
+        ls += __shfl_xor(ls, 32, 64);
+        l_run = l_run * corr + ls;
+        m_run = m_new;
+#pragma unroll
+        for (int db = 0; db < DB; db++)
+#pragma unroll
+          for (int v = 0; v < 16; v++) o[db][v] *= corr;
+      }
+      if constexpr (j + 1 < NB) {
+        constexpr int NEXT = (j + 1) % R;
+        stage(std::integral_constant<int, NEXT>{}, cur ^ 1);   // every wave left that buffer at the last barrier
+        if constexpr (j + 1 + R < NB) prefetch(std::integral_constant<int, NEXT>{}, b + 1 + R);
+      }
+      if (live) {
+        // O^T += V^T P^T over two 16-key steps; step u uses the lane's own values v = 8u .. 8u+7,
+        // i.e. keys 16u + 8*(e/4) + 4g + e%4, and V^T supplies the same keys per dim.
+#pragma unroll
+        for (int u = 0; u < 2; u++) {
+          float x[8];
+#pragma unroll
+          for (int e = 0; e < 8; e++) x[e] = pv[8 * u + e];
+          u32x4_t phi, plo;
+          split8(x, phi, plo);
+#pragma unroll
+          for (int db = 0; db < DB; db++) {
+            const unsigned char *vp = vt_lds + (db * 32 + c) * VSTR + (16 * u + 4 * g) * 2;
+            const u32x2_t v0 = *(const u32x2_t *)vp, v1 = *(const u32x2_t *)(vp + 16);
+            const u32x4_t vf = {v0.x, v0.y, v1.x, v1.y};
+            o[db] = mfma_bf16(vf, phi, o[db]);
+            o[db] = mfma_bf16(vf, plo, o[db]);
+          }
+        }
+      }
+      if constexpr (j + 1 < NB) __syncthreads();             // block j+1 staged; everyone is done with block j
+    });
+  };
+  if (part < kAttnNear / kAttnPart) run(std::integral_constant<int, kAttnPart / 32>{});
+  else run(std::integral_constant<int, kAttnFarPart / 32>{});
   if (!valid_q) return;
   float *dst = a.part + (((size_t)i * a.hq + hk * G + gh) * a.max_parts + part) * (HD + 2);
   if (g == 0) { dst[0] = m_run; dst[1] = l_run; }
@@ -544,10 +581,10 @@ static hipError_t launch_thg(AttnArgs a, int max_pos, hipStream_t st) {
     a.bulk_blocks = (a.bulk_keys + 31) / 32;
     a.bulk_parts = attn_parts_covering(a.bulk_keys);
     if (a.bulk_parts + 1 > a.max_parts) return hipErrorInvalidValue;
+    // At least four wavefronts per bulk workgroup, also for fewer than four blocks of 32 query rows: the ones
+    // without rows still take their share of loading and staging the K/V blocks.
     const int qblocks = (a.rows * G + 31) / 32;
-    if (qblocks <= 1) e = launch_hybrid<HD, G, 1>(a, 1, st);
-    else if (qblocks <= 2) e = launch_hybrid<HD, G, 2>(a, 1, st);
-    else if (qblocks <= 4) e = launch_hybrid<HD, G, 4>(a, 1, st);
+    if (qblocks <= 4) e = launch_hybrid<HD, G, 4>(a, 1, st);
     else e = launch_hybrid<HD, G, 8>(a, (qblocks + 7) / 8, st);
   } else {
     a.tail_only = 0;

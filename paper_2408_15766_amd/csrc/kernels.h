@@ -100,15 +100,6 @@ struct AttnArgs {
   int max_parts;
   void *out;
   int tail_only, bulk_keys, bulk_blocks, bulk_parts, q_groups;   // set by launch_attention (hybrid matrix-core / vector split)
-  // Optional (bf16 storage only): take the rows of this launch straight from the QKV projection.  `q` and the cache
-  // rows of the launch's own rows are then not read: queries, keys and values are the sums of the projection's K-split
-  // partials (columns: q heads, k heads, v heads; split s of row i at qkv_part + (s * qkv_mpad + i) * qkv_ld), queries
-  // and keys rotated by rope[i], and each row's key and value are also written to its cache slot.  The rows' slots must
-  // be consecutive: slot[i] = slot[0] + i.  What launch_reduce_rope_kv followed by the plain form computes, bit for bit.
-  const float *qkv_part;
-  int qkv_split, qkv_mpad, qkv_ld;
-  const float2 *rope;                   // [rows][hd/2] (cos, sin)
-  const int *slot;                      // [rows]
 };
 hipError_t launch_attention(int dtype, const AttnArgs &a, int max_pos, hipStream_t st);
 
