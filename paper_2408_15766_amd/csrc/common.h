@@ -27,10 +27,19 @@ template <typename T> __device__ __forceinline__ T from_f32(float x);
 template <> __device__ __forceinline__ float from_f32<float>(float x) { return x; }
 template <> __device__ __forceinline__ bf16_t from_f32<bf16_t>(float x) { bf16_t r; r.v = f32_to_bf16_bits(x); return r; }
 
-// Rotary embedding of the plane (a, b) = (dim j, dim j + hd/2) by (cos, sin).  Written with explicitly rounded
-// products and sums (no fused multiply-add), so every kernel that rotates the same inputs gets the same bits.
-__device__ __forceinline__ float rope_first(float a, float b, float2 cs) { return __fsub_rn(__fmul_rn(a, cs.x), __fmul_rn(b, cs.y)); }
-__device__ __forceinline__ float rope_second(float a, float b, float2 cs) { return __fadd_rn(__fmul_rn(b, cs.x), __fmul_rn(a, cs.y)); }
+// Rotary embedding of the plane (a, b) = (dim j, dim j + hd/2) by (cos, sin).  Contraction into fused multiply-adds is
+// switched off here: which product the compiler would fuse depends on the surrounding code, and every kernel that
+// rotates the same inputs has to get the same bits.
+__device__ __forceinline__ float rope_first(float a, float b, float2 cs) {
+#pragma clang fp contract(off)
+  const float x = a * cs.x, y = b * cs.y;
+  return x - y;
+}
+__device__ __forceinline__ float rope_second(float a, float b, float2 cs) {
+#pragma clang fp contract(off)
+  const float x = b * cs.x, y = a * cs.y;
+  return x + y;
+}
 
 // Butterfly reductions over the 64 lanes of a wavefront; every lane gets the result.
 // The exchange pattern is fixed, so the result does not depend on the data.
