@@ -25,7 +25,7 @@ if ROOT not in sys.path:
 HBM_PEAK_GBPS = 8000.0
 # HBM bytes per GEMM launch (fetch + write) measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by a
 # plain-copy calibration: see profiles/traffic_gemm_stream_<workload>.txt.  None where not measured.
-MEASURED_TRAFFIC_BYTES_PER_LAUNCH = {"llama2-7b": 113.5e6}
+MEASURED_TRAFFIC_BYTES_PER_LAUNCH = {"llama2-7b": 113.0e6}
 
 
 # Mean acceptance length the paper reports for its trained drafts (Table 1, mean over its three benchmarks), per model
