@@ -104,31 +104,43 @@ def cpu_baseline(sh, layers_timed=2):
     tsh = sh.with_(n_layers=layers_timed)
     w = as_dtype(wl.make_weights(tsh), np.float32)
     prompt = wl.make_prompt(tsh)
-    st, _ = oracle.prefill(w, tsh, prompt, len(prompt) + 256, dtype=np.float32)
-    t0 = time.perf_counter()
-    st.cycle = 1
-    tree = oracle.draft_tree(st, tsh.tree_depth, tsh.tree_topk, tsh.tree_total)
-    t1 = time.perf_counter()
-    logits, feats = oracle.verify_tree(st, tree)
-    acc, bonus = oracle.accept_greedy(tree, logits)
-    emitted = oracle.commit(st, tree, feats, acc, bonus)
-    t2 = time.perf_counter()
-    # one more layer over the same rows, to extrapolate linearly in depth
+    st, _ = oracle.prefill(w, tsh, prompt, len(prompt) + 512, dtype=np.float32)
+    # whole cycles until about ten seconds of CPU work have been timed
+    draft_s = verify_s = 0.0
+    cycles = emitted_total = 0
+    while cycles < 48 and draft_s + verify_s < 10.0:
+        t0 = time.perf_counter()
+        st.cycle = cycles + 1
+        tree = oracle.draft_tree(st, tsh.tree_depth, tsh.tree_topk, tsh.tree_total)
+        t1 = time.perf_counter()
+        logits, feats = oracle.verify_tree(st, tree)
+        acc, bonus = oracle.accept_greedy(tree, logits)
+        emitted = oracle.commit(st, tree, feats, acc, bonus)
+        t2 = time.perf_counter()
+        draft_s += t1 - t0
+        verify_s += t2 - t1
+        cycles += 1
+        emitted_total += len(emitted)
+    # more layers over the rows of the last tree, to extrapolate linearly in depth
     n = st.n - len(emitted)                                   # the verified rows still sit at slots n + j
     rows = tree.n_nodes
     h = np.random.default_rng(0).standard_normal((rows, tsh.d_model)).astype(np.float32)
     vis = [list(range(n)) + [n + a for a in tree.path(j)] for j in range(rows)]
+    reps = 8
     t3 = time.perf_counter()
-    oracle.decoder_layer(h, w, "layers.0.", tsh, 0, st.tcache, (n + tree.depth).astype(np.int64),
-                         [n + j for j in range(rows)], vis)
+    for _ in range(reps):
+        oracle.decoder_layer(h, w, "layers.0.", tsh, 0, st.tcache, (n + tree.depth).astype(np.int64),
+                             [n + j for j in range(rows)], vis)
     t4 = time.perf_counter()
-    draft_s, verify_s, layer_s = t1 - t0, t2 - t1, t4 - t3
-    full_cycle = draft_s + verify_s + (sh.n_layers - layers_timed) * layer_s
+    layer_s = (t4 - t3) / reps
+    cycle_s = (draft_s + verify_s) / cycles
+    full_cycle = cycle_s + (sh.n_layers - layers_timed) * layer_s
     return {
-        "value": len(emitted) / full_cycle, "unit": "tokens/s", "cores": blas_threads(), "kind": "oracle",
-        "sample": f"1 cycle on a {layers_timed}-layer truncation at full width (draft {draft_s:.2f} s, verify {verify_s:.2f} s), "
-                  f"extrapolated to {sh.n_layers} layers with one timed decoder layer ({layer_s:.2f} s); numpy fp32",
-        "measured_truncated_cycle_s": draft_s + verify_s,
+        "value": emitted_total / cycles / full_cycle, "unit": "tokens/s", "cores": blas_threads(), "kind": "oracle",
+        "sample": f"{cycles} cycles on a {layers_timed}-layer truncation at full width ({draft_s + verify_s:.1f} s: draft "
+                  f"{draft_s / cycles:.2f} s and verify {verify_s / cycles:.2f} s per cycle), extrapolated to {sh.n_layers} layers "
+                  f"with a timed decoder layer ({layer_s:.3f} s, mean of {reps}); numpy fp32",
+        "measured_truncated_cycle_s": cycle_s,
     }
 
 
