@@ -41,6 +41,14 @@ __device__ __forceinline__ float rope_second(float a, float b, float2 cs) {
   return x + y;
 }
 
+// A store of a result that the NEXT kernel reads (on other XCDs), written through to device scope right away
+// instead of staying dirty in this XCD's L2 until the end-of-kernel write-back.  Pays for the GEMM's partial sums
+// (the reducing kernel that follows starts ~1 % of a cycle earlier, summed over a forward); the same for the row
+// kernels changes nothing and for the attention partials, many small stores per lane, it costs 7 % of a verify.
+__device__ __forceinline__ void store_through(float *p, float v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
 // Butterfly reductions over the 64 lanes of a wavefront; every lane gets the result.
 // The exchange pattern is fixed, so the result does not depend on the data.
 __device__ __forceinline__ float wave_sum(float x) {

@@ -255,7 +255,7 @@ __global__ __launch_bounds__(kGemmThreads, (TB <= 2 && kStages <= 3) ? 2 : 1) vo
 #pragma unroll
     for (int v = 0; v < 16; v++) {
       const int i = t * 32 + 8 * (v >> 2) + 4 * g + (v & 3);
-      if (i < m_loc) out[(size_t)i * a.ldp] = acc[t][v];
+      if (i < m_loc) store_through(&out[(size_t)i * a.ldp], acc[t][v]);
     }
 }
 
