@@ -45,18 +45,19 @@ def sample_children(q_logits_row: np.ndarray, temperature: float, m: int, seed: 
 
 
 def accept_qratio(token: Sequence[int], parent: Sequence[int], p_logits: np.ndarray, q_logits: np.ndarray, temperature: float,
-                  seed: int, cycle: int, max_depth: int = 15) -> Tuple[List[int], int, float]:
+                  seed: int, cycle: int, max_depth: int = None) -> Tuple[List[int], int, float]:
     """Walk the tree from the root (node 0; parents precede children; the children of a node are tried in node
     order, which must be their draw order).  p_logits[i], q_logits[i]: target / draft logits AT node i (they
     score node i's children).  -> (accepted nodes, next token, margin): margin is the smallest relative distance
     |u q - p| / p of any accept/reject decision taken, so that a caller comparing against an fp32 evaluation
-    can set aside the draws that rounding could flip."""
+    can set aside the draws that rounding could flip.  max_depth: a caller that caps the tokens accepted per cycle
+    passes its cap (the walk then stops at that depth and draws the next token there); None = no cap."""
     n = len(token)
     cur, acc, margin = 0, [], np.inf
     while True:
         p = _softmax64(p_logits[cur] / temperature)
         q = _softmax64(q_logits[cur] / temperature)
-        kids = [c for c in range(cur + 1, n) if parent[c] == cur] if len(acc) < max_depth else []
+        kids = [c for c in range(cur + 1, n) if parent[c] == cur] if max_depth is None or len(acc) < max_depth else []
         moved = False
         for j, c in enumerate(kids):
             x = int(token[c])

@@ -10,8 +10,13 @@ oracle/qratio.py).  Every node that has children is run through the draft model 
 in one forward, exactly as the dynamic tree's expansion steps are.  With sampled children the acceptance is
 the ratio rule of oracle/qratio.py; with deterministic children it is the point-mass rule of oracle/spec.py.
 
-reading: the paper fixes no particular shape; any shape within the limits below is accepted (at most 128 nodes,
-depth 15, 16 proposals per node, 16 expanded nodes per depth).
+reading: the paper fixes no particular shape, so any tree is accepted: parents before children, and the
+children of a node carrying distinct ranks.  Sampled children have one more condition, which the acceptance rule
+itself imposes: the ratio rule tries the children of a node as successive draws without replacement from the
+draft distribution, so they must BE the first c draws, in draw order (ranks 0, 1, ..., c-1 in node order).  A
+child of rank r whose earlier draws are missing from the tree follows the marginal of the (r+1)-th draw, not
+the renormalised draft distribution the rule divides by, and the output would no longer be target-distributed
+(tests/test_oracle_static_tree.py shows the chi-square test failing for such a shape).
 """
 from __future__ import annotations
 
@@ -32,22 +37,23 @@ class StaticShape:
 
     def __post_init__(self):
         n = len(self.parent)
-        assert n == len(self.rank) and 1 <= n <= 128 and self.parent[0] == -1
+        assert n == len(self.rank) and n >= 1 and self.parent[0] == -1
         self.depth = [0] * n
         for i in range(1, n):
-            assert 0 <= self.parent[i] < i and 0 <= self.rank[i] < 16
+            assert 0 <= self.parent[i] < i, "a parent precedes its children"
+            assert self.rank[i] >= 0
             self.depth[i] = self.depth[self.parent[i]] + 1
-            assert self.depth[i] >= self.depth[i - 1] and self.depth[i] <= 15, "nodes in order of depth, depth <= 15"
-        last = {}
-        for i in range(1, n):
-            assert self.rank[i] > last.get(self.parent[i], -1), "the children of a node are listed in increasing rank"
-            last[self.parent[i]] = self.rank[i]
         self.n_nodes = n
         self.children = [[i for i in range(1, n) if self.parent[i] == u] for u in range(n)]
+        for u in range(n):
+            ranks = [self.rank[c] for c in self.children[u]]
+            assert len(set(ranks)) == len(ranks), "the children of a node carry distinct ranks"
         self.expanded = [u for u in range(n) if self.children[u]]           # nodes run through the draft model
         self.width = [1 + max((self.rank[c] for c in self.children[u]), default=-1) for u in range(n)]
-        for t in range(1, 16):
-            assert sum(1 for u in self.expanded if self.depth[u] == t) <= 16, "at most 16 expanded nodes per depth"
+
+    def children_are_successive_draws(self) -> bool:
+        """True when every node's children have ranks 0, 1, ..., c-1 in node order (what sampled children need)."""
+        return all([self.rank[c] for c in self.children[u]] == list(range(len(self.children[u]))) for u in range(self.n_nodes))
 
     @staticmethod
     def chain(length: int) -> "StaticShape":
@@ -59,6 +65,7 @@ def draft_static(st: SpecState, shape_: StaticShape, temperature: float = 0.0, s
     """-> (tree, q_logits [n_nodes, V]: the draft's logit row at every expanded node, zeros elsewhere)."""
     w, shape, n = st.w, st.shape, st.n
     ss = shape_
+    assert not sampled or ss.children_are_successive_draws(), "sampled children must be the first draws, in draw order"
     m1 = len(st.pend_tokens)
     pos = np.arange(n - m1 + 1, n + 1)
     logits, g = draft_forward(w, shape, st.dcache, st.pend_feats, st.pend_tokens, pos, list(pos),

@@ -77,6 +77,54 @@ def test_shape_validation():
     with pytest.raises(AssertionError):
         StaticShape([-1, 0, 0], [0, 1, 1])                    # two children with the same rank
     with pytest.raises(AssertionError):
-        StaticShape([-1, 0, 1, 0], [0, 0, 0, 1])              # not in order of depth
+        StaticShape([-1, 2, 0], [0, 0, 0])                    # a child before its parent
     with pytest.raises(AssertionError):
-        StaticShape([-1, 0], [0, 16])                         # rank beyond the proposal limit
+        StaticShape([0, 0], [0, 0])                           # node 0 is not a root
+    # what the paper leaves open is accepted: any order of the nodes that keeps parents first, any rank, any size
+    ss = StaticShape([-1, 0, 1, 0], [0, 0, 0, 1])             # not in order of depth
+    assert ss.depth == [0, 1, 2, 1]
+    big = StaticShape([-1] + list(range(40)) + [0] * 200, [0] * 41 + list(range(2, 202)))   # depth 40, 241 nodes, rank 201
+    assert big.n_nodes == 241 and max(big.depth) == 40 and big.width[0] == 202
+    assert not big.children_are_successive_draws() and StaticShape.chain(3).children_are_successive_draws()
+
+
+def test_unordered_and_deep_shapes_leave_greedy_output_unchanged(tiny):
+    sh, w, prompt = tiny
+    want = greedy_decode(w, sh, prompt, 16)
+    for ss in (StaticShape([-1, 0, 1, 0, 3, 2], [0, 0, 0, 1, 0, 1]),        # depths 0 1 2 1 2 3: not depth-major
+               StaticShape.chain(18),                                       # deeper than any product limit
+               StaticShape([-1] + [0] * 20, [0] + list(range(20)))):        # 20 proposals at the root
+        got, _ = spec_decode_static(w, sh, prompt, 16, ss)
+        assert got == want
+
+
+def test_sampled_children_must_be_the_first_draws(tiny):
+    """Why sampled shapes may not skip a rank: the ratio rule divides by the draft distribution renormalised over
+    the tokens not yet listed, which is the law of a child only if every earlier draw is listed before it.  With a
+    12-token vocabulary and a draft that disagrees with the target, listing draws (0, 1) keeps the emitted token
+    target-distributed; listing only draw 1 does not."""
+    rng = np.random.default_rng(5)
+    V, n = 12, 30000
+    p_log, q_log = rng.standard_normal(V) * 1.5, rng.standard_normal(V) * 1.5
+    p = np.exp(p_log - p_log.max()); p /= p.sum()
+
+    def pvalue(listed):
+        counts = np.zeros(V)
+        rows_p, rows_q = np.tile(p_log, (1 + len(listed), 1)), np.tile(q_log, (1 + len(listed), 1))
+        for seed in range(n):
+            draws = qratio.sample_children(q_log, 1.0, 2, seed, 1, 0)
+            kids = [draws[i] for i in listed]
+            acc, nxt, _ = qratio.accept_qratio([0] + kids, [-1] + [0] * len(kids), rows_p, rows_q, 1.0, seed, 1)
+            counts[kids[acc[0] - 1] if acc else nxt] += 1
+        return stats.chisquare(counts, p * n).pvalue
+
+    assert pvalue([0, 1]) > 0.01
+    assert pvalue([1]) < 1e-6
+    sh, w, prompt = tiny
+    st, _ = prefill(w, sh, prompt, 64, temperature=1.0, seed=0)
+    st.cycle = 1
+    for parent, rank in (([-1, 0], [0, 1]), ([-1, 0, 0], [0, 0, 2]), ([-1, 0, 0], [0, 1, 0])):
+        with pytest.raises(AssertionError):
+            draft_static(st, StaticShape(parent, rank), 1.0, True, 0)
+        draft_static(st.__class__(**{**st.__dict__, "tcache": st.tcache.copy(), "dcache": st.dcache.copy()}),
+                     StaticShape(parent, rank))                # the same shapes are fine with deterministic children
