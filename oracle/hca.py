@@ -15,16 +15,16 @@ offset o = t - s, the key/value used is the one of stream J-1-o if o <= J-2 and
 of stream 0 otherwise.  With J = 1 this is plain causal attention (Sec. 3.2,
 first step).
 
-Algorithm (appendix A.1, attention): scores against stream 0 under the causal
-mask; for the i-th diagonal below the main one (i = 0 is the main diagonal)
-overwrite the scores by those against stream J-1-i; softmax; values of stream 0
-weighted by the probabilities; then, along the same diagonals, add
-probability * (value of stream J-1-i  -  value of stream 0).
+The function below is that definition written out: for every query it gathers,
+position by position, the key and the value of the stream the rule names, and
+runs plain softmax attention over them.
 
-reading: the appendix multiplies the value correction by the scores taken
-BEFORE the softmax.  That cannot be meant (it would not be an attention over
-the mixed key/value set of the Sec. 3.2 formula, and step j would not equal j
-autoregressive draft calls); the probabilities after the softmax are used.
+reading: the appendix reaches the same thing in a batched way (target-stream
+scores with some diagonals replaced, then a correction of the output along those
+diagonals), but its correction is weighted by the scores taken BEFORE the
+softmax.  That cannot be meant (it would not be an attention over the mixed
+key/value set of the Sec. 3.2 formula, and step j would not equal j
+autoregressive draft calls); the softmax probabilities weight every value.
 """
 from __future__ import annotations
 
@@ -32,7 +32,7 @@ from typing import List, Optional, Sequence
 
 import numpy as np
 
-from .llama import Weights, rmsnorm, rope, _identity
+from .llama import Weights, attention_row, rmsnorm, rope, _identity
 
 
 def hca_attention(q: np.ndarray, ks: Sequence[np.ndarray], vs: Sequence[np.ndarray],
@@ -43,28 +43,15 @@ def hca_attention(q: np.ndarray, ks: Sequence[np.ndarray], vs: Sequence[np.ndarr
     n_streams = len(ks)
     t_len, hq, hd = q.shape
     group = hq // ks[0].shape[1]
+    k_all, v_all = np.stack(ks), np.stack(vs)                   # [stream, position, kv head, hd]
     out = np.zeros_like(q)
-    rows = np.arange(t_len)
-    future = rows[None, :] > rows[:, None]                      # [query, key]
     for h in (range(hq) if heads is None else heads):
         kv = h // group
-        qh = q[:, h]
-        score = qh @ ks[0][:, kv].T / np.sqrt(np.asarray(hd, dtype=q.dtype))
-        score[future] = -np.inf
-        for i in range(n_streams - 1):
-            m = n_streams - 1 - i
-            alt = qh @ ks[m][:, kv].T / np.sqrt(np.asarray(hd, dtype=q.dtype))
-            tq = rows[i:]
-            score[tq, tq - i] = alt[tq, tq - i]
-        score = score - score.max(axis=1, keepdims=True)
-        prob = np.exp(score)
-        prob = prob / prob.sum(axis=1, keepdims=True)
-        o = prob @ vs[0][:, kv]
-        for i in range(n_streams - 1):
-            m = n_streams - 1 - i
-            tq = rows[i:]
-            o[tq] += prob[tq, tq - i][:, None] * (vs[m][tq - i, kv] - vs[0][tq - i, kv])
-        out[:, h] = o
+        for t in range(t_len):
+            s = np.arange(t + 1)                                # key positions of query t
+            o = t - s                                           # how far back each one lies
+            stream = np.where(o <= n_streams - 2, n_streams - 1 - o, 0)
+            out[t, h] = attention_row(q[t, h], k_all[stream, s, kv], v_all[stream, s, kv])
     return out
 
 
