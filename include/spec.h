@@ -189,7 +189,12 @@ int spec_set_graphs(spec_ctx *ctx, int32_t enable);
  * -1).  rank[i] says which of its parent's proposals node i is: the rank-th
  * best token of the draft distribution at the parent, or, with sampled != 0
  * (needs cfg.temperature > 0), the rank-th of the tokens DRAWN from it without
- * replacement.  The children of a node must be listed in increasing rank; a
+ * replacement.  The children of a node must be listed in increasing rank; with
+ * sampled != 0 they must carry the ranks 0, 1, ..., c-1 without gaps (the ratio
+ * rule treats the j-th listed child as the j-th draw: a child whose earlier
+ * draws are not in the tree would not follow the distribution the rule
+ * divides by, and the output would lose the target distribution); shapes with
+ * gaps are for deterministic children only.  A
  * depth may have at most 16 nodes with children; the nodes with children
  * (root excluded) may not exceed cfg.tree_depth * cfg.tree_topk (the draft
  * scratch the workspace was sized for).  spec_draft_tree then drafts this shape

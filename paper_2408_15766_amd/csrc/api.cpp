@@ -879,7 +879,7 @@ struct StaticPlan {                   // host-side analysis of a static shape
   spec_ctx::StaticHost h;
 };
 // Validates a shape and derives its tables; returns nullptr or the reason it is not accepted.
-const char *plan_static(int n, const int32_t *parent, const int32_t *rank, StaticPlan *p) {
+const char *plan_static(int n, const int32_t *parent, const int32_t *rank, bool sampled, StaticPlan *p) {
   if (n < 1 || n > kMaxNodes || !parent || !rank) return "n_nodes outside 1..128 or NULL arrays";
   if (parent[0] != -1) return "node 0 must be the root (parent -1)";
   int kids[kMaxNodes] = {}, last_rank[kMaxNodes];
@@ -895,6 +895,10 @@ const char *plan_static(int n, const int32_t *parent, const int32_t *rank, Stati
     if (p->depth[i] > kMaxDepth) return "deeper than 15";
     if (rank[i] < 0 || rank[i] >= kMaxTopK) return "rank outside 0..15";
     if (rank[i] <= last_rank[u]) return "the children of a node must be listed in increasing rank";
+    // The ratio rule tries a node's children as successive draws without replacement, each against the draft
+    // distribution renormalised over the tokens not listed before it: that is the law of a child only if every
+    // earlier draw is in the tree, so sampled children must carry ranks 0, 1, ..., c-1.
+    if (sampled && rank[i] != last_rank[u] + 1) return "sampled children of a node must carry ranks 0, 1, ... without gaps";
     last_rank[u] = rank[i];
     kids[u]++;
     p->h.width[p->depth[u]] = std::max(p->h.width[p->depth[u]], rank[i] + 1);
@@ -921,7 +925,7 @@ size_t static_table_ints() { return (size_t)6 * kMaxNodes + (kMaxDepth + 1) * kM
 
 uint64_t spec_static_tree_bytes(const spec_config *cfg, int32_t n_nodes, const int32_t *parent, const int32_t *rank, int32_t sampled) {
   StaticPlan p;
-  if (!cfg || plan_static(n_nodes, parent, rank, &p) != nullptr) return 0;
+  if (!cfg || plan_static(n_nodes, parent, rank, sampled != 0, &p) != nullptr) return 0;
   size_t bytes = align_up(static_table_ints() * 4);
   if (sampled) bytes += align_up((size_t)(p.h.n_expanded + (p.h.rows[0] ? 1 : 0)) * cfg->vocab * 4);
   return bytes;
@@ -934,7 +938,7 @@ int spec_set_static_tree(spec_ctx *c, int32_t n_nodes, const int32_t *parent, co
   if (n_nodes == 0) { c->st = spec_ctx::StaticHost{}; return SPEC_OK; }          // back to the dynamic tree
   const spec_config &g = c->cfg;
   StaticPlan p;
-  const char *why = plan_static(n_nodes, parent, rank, &p);
+  const char *why = plan_static(n_nodes, parent, rank, sampled != 0, &p);
   if (why) return fail(c, SPEC_EINVAL, "set_static_tree: %s", why);
   if (n_nodes > g.tree_total) return fail(c, SPEC_ECAP, "set_static_tree: %d nodes exceed the configured tree_total %d", n_nodes, g.tree_total);
   if (p.h.n_expanded > g.tree_depth * g.tree_topk)

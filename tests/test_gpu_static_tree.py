@@ -16,7 +16,9 @@ pytestmark = pytest.mark.gpu
 EAGLE_LIKE = StaticShape(parent=[-1, 0, 0, 0, 0, 1, 1, 1, 2, 2, 3, 5, 5, 6, 11],
                          rank=[0, 0, 1, 2, 3, 0, 1, 2, 0, 1, 0, 0, 1, 0, 0])
 SHAPES = {"chain1": StaticShape.chain(1), "chain5": StaticShape.chain(5), "tree15": EAGLE_LIKE,
-          "wide": StaticShape(parent=[-1] + [0] * 16 + [1, 1, 16], rank=[0] + list(range(16)) + [0, 3, 2])}
+          "wide": StaticShape(parent=[-1] + [0] * 16 + [1, 1, 16], rank=[0] + list(range(16)) + [0, 3, 2]),
+          # the same width with gap-free ranks: what sampled children need (each child is the next draw)
+          "wide_draws": StaticShape(parent=[-1] + [0] * 16 + [1, 1, 16], rank=[0] + list(range(16)) + [0, 1, 0])}
 CAP = (6, 8, 40)            # configured capacity: depth * top-k bounds the expanded nodes, total bounds the nodes
 
 
@@ -87,7 +89,7 @@ def test_static_tree_point_mass_rule_matches_oracle(env, tiny_gpu):
     assert got == want and taus == wt
 
 
-@pytest.mark.parametrize("name,seed", [("tree15", 1), ("tree15", 2), ("chain5", 3), ("wide", 4)])
+@pytest.mark.parametrize("name,seed", [("tree15", 1), ("tree15", 2), ("chain5", 3), ("wide_draws", 4)])
 def test_static_tree_sampled_children_match_oracle(env, tiny_gpu, name, seed):
     torch, P = env
     sh, hw, w64, prompt, dw = tiny_gpu
@@ -123,6 +125,13 @@ def test_static_tree_errors_and_return_to_dynamic(env, tiny_gpu):
         eng.set_static_tree([-1] + list(range(45)), [0] * 46)            # more nodes than tree_total = 40
     with pytest.raises(P.SpecError):
         eng.set_static_tree([-1, 0], [0, 0], sampled=True)               # sampled children need T > 0
+    hot = P.Engine(sh, dw, tree=CAP, temperature=1.0, seed=1)
+    for parent, rank in [([-1, 0], [0, 1]), ([-1, 0, 0], [0, 0, 2]), (SHAPES["wide"].parent, SHAPES["wide"].rank)]:
+        with pytest.raises(P.SpecError) as e:                             # sampled children with a rank skipped
+            hot.set_static_tree(parent, rank, sampled=True)
+        assert e.value.code == P.binding.SPEC_EINVAL
+        hot.set_static_tree(parent, rank)                                 # fine with deterministic children
+    hot.close()
     # a shape, then back to the dynamic tree: the dynamic result is the one of a fresh context
     eng.set_static_tree(EAGLE_LIKE.parent, EAGLE_LIKE.rank)
     first = eng.prefill(prompt)
