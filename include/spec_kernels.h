@@ -54,6 +54,21 @@ int spec_k_attention(int32_t dtype, const void *q, const void *kcache, const voi
 int spec_k_topk_logprob(const float *logits, int32_t rows, int32_t vocab, int32_t k, float *scratch_f, int32_t *scratch_i,
                         int32_t *top_tok, float *top_lp, void *stream);
 
+/* spec_k_topk_logprob for callers that cannot allocate device memory and have no
+ * scratch to pass: code under HIP graph capture, tight serving loops, harnesses
+ * that forbid hipMalloc.  Same kernels, inputs, outputs and results as
+ * spec_k_topk_logprob; the scratch is a fixed array inside the library (136 KiB
+ * per GPU the library runs on, held until the process ends), which bounds the
+ * vocabulary: vocab <= SPEC_STATIC_TOPK_MAX_VOCAB, larger ones return SPEC_ECAP.
+ * The call allocates nothing and launches on `stream`, which must belong to the
+ * CURRENT device (the array's address is looked up per device, on the first
+ * call there).  All calls on one GPU share the array: calls that may overlap
+ * (different streams, different threads) race; calls on one stream do not.
+ * Nothing in the array needs clearing between calls. */
+#define SPEC_STATIC_TOPK_MAX_VOCAB 262144
+int spec_k_topk_logprob_static(const float *logits, int32_t rows, int32_t vocab, int32_t k, int32_t *top_tok, float *top_lp,
+                               void *stream);
+
 /* Acceptance with SAMPLED draft tokens: the ratio rule of speculative sampling
  * (Sec. 2, third step: the modified rejection sampling it names; the rule of the
  * chain and static-tree comparison systems of Sec. 4.1).  The tree has n_nodes

@@ -88,6 +88,7 @@ lib.spec_k_attention.argtypes = [C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, 
                                  C.c_int32, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p]
 lib.spec_k_topk_logprob.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
                                     C.c_void_p, C.c_void_p]
+lib.spec_k_topk_logprob_static.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]
 lib.spec_k_accept_qratio.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_float, C.c_void_p, C.c_void_p, C.c_uint64,
                                      C.c_uint32, C.c_void_p, C.c_void_p, C.c_void_p]
 lib.spec_k_sample_children.argtypes = [C.c_void_p, C.c_int32, C.c_float, C.c_int32, C.c_uint64, C.c_uint32, C.c_uint32, C.c_void_p,
@@ -292,6 +293,19 @@ def spec_k_topk_logprob(logits, k: int):
                                  _stream_ptr())
     if rc:
         raise SpecError(rc, "spec_k_topk_logprob")
+    return tok[:, :k], lp[:, :k]
+
+
+def spec_k_topk_logprob_static(logits, k: int, top_tok=None, top_lp=None):
+    """The same call without scratch arguments (the library's static scratch).  top_tok / top_lp: optional preallocated
+    int32 / fp32 [rows, 16] outputs, so that a caller can keep the call itself free of allocations."""
+    import torch
+    rows, vocab = logits.shape
+    tok = torch.zeros((rows, 16), dtype=torch.int32, device=logits.device) if top_tok is None else top_tok
+    lp = torch.zeros((rows, 16), dtype=torch.float32, device=logits.device) if top_lp is None else top_lp
+    rc = lib.spec_k_topk_logprob_static(logits.data_ptr(), rows, vocab, k, tok.data_ptr(), lp.data_ptr(), _stream_ptr())
+    if rc:
+        raise SpecError(rc, "spec_k_topk_logprob_static")
     return tok[:, :k], lp[:, :k]
 
 

@@ -9,7 +9,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libspec.so")
-SOURCES = ["gemm.hip", "rowops.hip", "attention.hip", "hca.hip", "distill.hip", "select.hip", "api.cpp"]
+SOURCES = ["gemm.hip", "rowops.hip", "attention.hip", "hca.hip", "distill.hip", "select.hip", "noalloc.hip", "api.cpp"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 # packed fp32 instructions stay off (device code only; the host pass ignores the feature)
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
@@ -29,7 +29,7 @@ def build(verbose: bool = True, extra_flags=(), out: str = LIB, tag: str = "") -
     """Compile and link.  extra_flags / out / tag build a tuning variant next to the product library."""
     objdir = os.path.join(HERE, "_build" + tag)
     os.makedirs(objdir, exist_ok=True)
-    with ThreadPoolExecutor(max_workers=min(7, os.cpu_count() or 1)) as ex:
+    with ThreadPoolExecutor(max_workers=min(8, os.cpu_count() or 1)) as ex:
         objs = list(ex.map(lambda s: _compile(s, objdir, extra_flags), SOURCES))
     r = subprocess.run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", out] + objs, capture_output=True, text=True)
     if r.returncode != 0:
