@@ -3,11 +3,13 @@
 
 One "step" is one draft + verify + accept cycle (all hot-path stages) at batch 1, T = 0, on a
 synthetic random-init LLaMA2-7B-shaped model (bf16, prompt 512, dynamic tree depth 6 / top-k 10 /
-60 verified tokens).  Prints ONE JSON line: tokens/s over exactly --steps cycles, the roofline of the
-dominant kernel (the weight-streaming GEMM, timed with HIP events in a separate instrumented pass),
-and the CPU oracle timed on a bounded sample of the same workload.  Two separately labelled
-objects measure the training-side kernels against the matrix-core peak: `hca_attention` (Sec. 3.2) and `topk_loss`
-(Sec. 3.1).
+60 verified tokens).  Prints ONE JSON line: tokens/s over exactly --steps cycles; `roofline`: the verify
+step against the HBM peak ((weights + KV read + KV write) / verify time, HIP events on the library's stream),
+with the weight-streaming GEMM launches of the verify as its `kernel` sub-object (timed with HIP event pairs
+in a separate instrumented pass); `shapes`: the same measurements at the other benchmark shapes (LLaMA3-70B,
+LLaMA2-13B, LLaMA3-8B); and the CPU oracle timed on a bounded sample of the headline workload.  Two separately
+labelled objects measure the training-side kernels against the matrix-core peak: `hca_attention` (Sec. 3.2)
+and `topk_loss` (Sec. 3.1).
 """
 from __future__ import annotations
 
@@ -23,9 +25,24 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0
-# HBM bytes per GEMM launch (fetch + write) measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by a
-# plain-copy calibration: see profiles/traffic_gemm_stream_<workload>.txt.  None where not measured.
-MEASURED_TRAFFIC_BYTES_PER_LAUNCH = {"llama2-7b": 113.0e6}
+OTHER_SHAPES = ("llama3-70b", "llama2-13b", "llama3-8b")     # timed after the headline workload, largest first
+
+
+def measured_traffic(workload_name):
+    """HBM bytes (fetch + write) measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE and scaled by a plain-copy
+    calibration, read from the `key = value` lines at the end of profiles/traffic_gemm_stream_<workload>.txt:
+    (bytes per verify step over all its kernels, bytes per GEMM launch); None where no such file or line exists."""
+    import re
+    path = os.path.join(ROOT, "profiles", "traffic_gemm_stream_" + workload_name.replace("-", "_") + ".txt")
+    vals = {}
+    try:
+        for line in open(path):
+            m = re.match(r"^(\w+)\s*=\s*([0-9.eE+-]+)\s*$", line)
+            if m:
+                vals[m.group(1)] = float(m.group(2))
+    except OSError:
+        pass
+    return vals.get("verify_step_hbm_bytes"), vals.get("gemm_launch_hbm_bytes")
 
 
 # Mean acceptance length the paper reports for its trained drafts (Table 1, mean over its three benchmarks), per model
@@ -50,6 +67,8 @@ def parse():
     ap.add_argument("--no-hca", action="store_true", help="skip the training-attention measurement (separate object in the JSON line)")
     ap.add_argument("--no-loss", action="store_true", help="skip the distillation-loss measurement (separate object in the JSON line)")
     ap.add_argument("--no-roofline-pass", action="store_true", help="skip the instrumented passes (for profilers)")
+    ap.add_argument("--no-other-shapes", action="store_true",
+                    help="time only the --config workload (default: the other benchmark shapes follow, in `shapes`)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain 1 GiB device copy four times (known traffic, to scale rocprofv3's FETCH_SIZE/WRITE_SIZE)")
     return ap.parse_args()
@@ -253,47 +272,30 @@ def static_shape(name):
     raise SystemExit(f"bench.py: unknown static tree {name!r}")
 
 
-def main():
-    a = parse()
-    if a.gpus != 1:
-        print("bench.py: this build runs on one GPU only (batch-1 decode has no data-parallel units); use --gpus 1",
-              file=sys.stderr)
-        sys.exit(2)
+def measure_shape(sh, weights, steps, warmup, forced_accept_arg, static_tree="", roofline_pass=True, label_overridden=False):
+    """All decode-path measurements of one workload on resident weights -> dict (see main for the field meanings)."""
     import torch
     import workload as wl
     import paper_2408_15766_amd as P
-
-    if a.calibrate_copy:
-        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")       # 1 GiB
-        dst = torch.empty_like(src)
-        for _ in range(4):
-            dst.copy_(src)
-        torch.cuda.synchronize()
-        print(json.dumps({"calibrate_copy_bytes_read_per_launch": src.numel() * 4, "bytes_written_per_launch": src.numel() * 4}))
-        return
-    sh = wl.BY_NAME[a.config]
-    if a.layers:
-        sh = sh.with_(n_layers=a.layers, name=f"{sh.name}-{a.layers}layer")
-    if a.tree:
-        d_, k_, n_ = (int(x) for x in a.tree.split(","))
-        sh = sh.with_(tree_depth=d_, tree_topk=k_, tree_total=n_)
-    torch.cuda.set_device(0)
-    weights = P.pack_weights(wl.iter_device_weights(sh, "cuda"))
     prompt = wl.make_prompt(sh)
-    total_cycles = a.warmup + a.steps
+    total_cycles = warmup + steps
     max_seq = sh.prompt_len + (sh.tree_depth + 1) * (total_cycles + 1) + sh.tree_total + 32
+    static_name, _, static_mode = static_tree.partition(":")
+
+    def engine():
+        e = P.Engine(sh, weights, max_seq=max_seq)
+        if static_name:
+            e.set_static_tree(*static_shape(static_name), sampled=static_mode == "sampled")
+        return e
 
     # ---- pass A: the timed region ------------------------------------------------------------
-    eng = P.Engine(sh, weights, max_seq=max_seq)
-    static_name, _, static_mode = a.static_tree.partition(":")
-    if static_name:
-        eng.set_static_tree(*static_shape(static_name), sampled=static_mode == "sampled")
+    eng = engine()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     eng.prefill(prompt)
     torch.cuda.synchronize()
     prefill_s = time.perf_counter() - t0                      # not part of `value`: once per request, first call (cold)
-    run_cycles(eng, a.warmup)
+    run_cycles(eng, warmup)
     # The interpreter's cyclic collector walks every object torch created at import (tens of ms per full
     # collection); park those in the permanent generation so a collection cannot land inside the timed loop.
     gc.collect()
@@ -301,52 +303,49 @@ def main():
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     stamps = [t0]
-    emitted = run_cycles(eng, a.steps, stamps=stamps)
+    emitted = run_cycles(eng, steps, stamps=stamps)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     eng.close()
     per_cycle = sorted((b - a_) * 1e3 for a_, b in zip(stamps, stamps[1:]))
     pick = lambda f: per_cycle[min(len(per_cycle) - 1, int(f * len(per_cycle)))]
-    tokens_per_s = emitted / dt
-    ms_per_step = dt / a.steps * 1e3
+    ms_per_step = dt / steps * 1e3
 
-    # plain autoregressive decoding through the same kernels (tree = the root alone): the 1.00x reference
-    # (only at T = 0, where the emitted tokens are a function of the weights alone)
-    forced_accept = max(0, min(sh.tree_depth, a.forced_accept)) if sh.temperature == 0 and sh.tree_total > 1 and not static_name else 0
+    # plain autoregressive decoding through the same kernels (tree = the root alone): the 1.00x reference.
+    # The teacher-forced pass (T = 0 only, where the emitted tokens are a function of the weights alone) needs its stream.
+    forced_accept = max(0, min(sh.tree_depth, forced_accept_arg)) if sh.temperature == 0 and sh.tree_total > 1 and not static_name else 0
     plain_extra = (total_cycles * (forced_accept + 1) + 1 - total_cycles) if forced_accept else 0
     plain = P.Engine(sh, weights, max_seq=max_seq, tree=(1, 1, 1))
     stream = [plain.prefill(prompt)]
-    run_cycles(plain, a.warmup, stream)
+    run_cycles(plain, warmup, stream)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    pe = run_cycles(plain, a.steps, stream)
+    pe = run_cycles(plain, steps, stream)
     torch.cuda.synchronize()
     plain_dt = time.perf_counter() - t0
     run_cycles(plain, plain_extra, stream)                    # untimed: the continuation the forced mode grafts
     plain.close()
 
     by = wl.algorithmic_bytes(sh)
-    n_mid = sh.prompt_len + a.warmup + a.steps // 2
+    n_mid = sh.prompt_len + warmup + steps // 2
     kv_read = n_mid * by["kv_bytes_per_token"]
     kv_write = sh.tree_total * by["kv_bytes_per_token"]
+    verify_bytes = by["verify_weights"] + kv_read + kv_write
     out = {
-        "metric": f"tokens/s (bs=1, T={sh.temperature:g})", "value": tokens_per_s, "unit": "tokens/s", "n_gpus": 1, "steps": a.steps,
-        "warmup": a.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": sh.dtype, "data": "synthetic",
-        "config": {"workload": f"{sh.name} shape, random init N(0,0.02), prompt {sh.prompt_len} uniform tokens, "
-                               + (f"static tree {a.static_tree}" if static_name else
-                                  f"tree depth {sh.tree_depth} top-k {sh.tree_topk} total {sh.tree_total}")
-                               + f", T={sh.temperature:g}, batch 1"},
+        "workload": f"{sh.name} shape, random init N(0,0.02), prompt {sh.prompt_len} uniform tokens, "
+                    + (f"static tree {static_tree}" if static_name else f"tree depth {sh.tree_depth} top-k {sh.tree_topk} total {sh.tree_total}")
+                    + f", T={sh.temperature:g}, batch 1",
+        "tokens_per_s": emitted / dt, "steps": steps, "warmup": warmup,
         "ms_per_cycle": ms_per_step,
         "cycle_ms_p10_median_p90": [pick(0.1), pick(0.5), pick(0.9)],
-        "mean_accepted_length": emitted / a.steps,
+        "mean_accepted_length": emitted / steps,
         "plain_decode_tokens_per_s": pe / plain_dt,
-        "plain_decode_ms_per_token": plain_dt / a.steps * 1e3,
+        "plain_decode_ms_per_token": plain_dt / steps * 1e3,
+        "plain_decode_hbm_frac": (by["verify_weights"] + kv_read + by["kv_bytes_per_token"]) / (plain_dt / steps) / 1e9 / HBM_PEAK_GBPS,
         "prefill_ms": prefill_s * 1e3, "prefill_tokens_per_s": sh.prompt_len / prefill_s,
     }
-
-    tau = PAPER_TAU.get((wl.BY_NAME[a.config].name, 0 if sh.temperature == 0 else 1))
-    if tau and not (a.layers or a.tree or static_name):
+    tau = PAPER_TAU.get((sh.name, 0 if sh.temperature == 0 else 1))
+    if tau and not (label_overridden or static_name):
         out["projection_at_paper_tau"] = {
             "what": "PROJECTION, not a measurement: the paper's mean acceptance length (Table 1) divided by this run's "
                     "measured cycle time; the measured cycles themselves accept about one token",
@@ -357,10 +356,10 @@ def main():
     if forced_accept:
         eng = P.Engine(sh, weights, max_seq=max_seq)
         first = eng.prefill(prompt)
-        _, pos, ok0 = run_forced_cycles(eng, a.warmup, stream, 1, forced_accept)
+        _, pos, ok0 = run_forced_cycles(eng, warmup, stream, 1, forced_accept)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        fe, pos, ok1 = run_forced_cycles(eng, a.steps, stream, pos, forced_accept)
+        fe, pos, ok1 = run_forced_cycles(eng, steps, stream, pos, forced_accept)
         torch.cuda.synchronize()
         fdt = time.perf_counter() - t0
         eng.close()
@@ -368,47 +367,113 @@ def main():
             "what": "every drafted tree has the known greedy continuation grafted in on the host (random-init drafts never "
                     "match the target), so the accept, compaction and hand-off stages run at a paper-like acceptance length; "
                     "the host-side tree edit is inside the timed loop",
-            "mean_accepted_length": fe / a.steps, "tokens_per_s": fe / fdt, "ms_per_cycle": fdt / a.steps * 1e3,
+            "mean_accepted_length": fe / steps, "tokens_per_s": fe / fdt, "ms_per_cycle": fdt / steps * 1e3,
             "speedup_over_plain_decode_same_kernels": (fe / fdt) / (pe / plain_dt),
             "tokens_equal_plain_decoding": bool(first == stream[0] and ok0 and ok1)}
+        out["tokens_equal_plain_decoding"] = out["teacher_forced"]["tokens_equal_plain_decoding"]
 
-    # ---- pass B / C: instrumented with HIP events on the library's stream ---------------------
-    if not a.no_roofline_pass:
+    # ---- instrumented passes with HIP events on the library's stream --------------------------
+    # level 1: one event pair around each call (draft, verify, accept) of the graph-replayed run;
+    # level 2: one pair around every GEMM launch, kernels launched individually (perturbs the pipeline: its own pass).
+    if roofline_pass:
+        step_traffic, launch_traffic = (None, None) if (label_overridden or static_name) else measured_traffic(sh.name)
         for level in (1, 2):
-            eng = P.Engine(sh, weights, max_seq=max_seq)
-            if static_name:
-                eng.set_static_tree(*static_shape(static_name), sampled=static_mode == "sampled")
+            eng = engine()
             eng.prefill(prompt)
-            run_cycles(eng, a.warmup)
+            run_cycles(eng, warmup)
             P.spec_set_profile(eng.ctx, level)
-            run_cycles(eng, a.steps)
+            run_cycles(eng, steps)
             ms, cnt = P.spec_get_profile(eng.ctx)
             eng.close()
             if level == 1:
                 draft_ms, verify_ms, accept_ms = (ms[i] / max(cnt[i], 1) for i in range(3))
+                gbps = verify_bytes / (verify_ms * 1e-3) / 1e9
                 out.update({"draft_ms": draft_ms, "verify_ms": verify_ms, "accept_ms": accept_ms,
-                            "verify_hbm_gbps": (by["verify_weights"] + kv_read + kv_write) / (verify_ms * 1e-3) / 1e9,
-                            "verify_hbm_frac": (by["verify_weights"] + kv_read + kv_write) / (verify_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS})
+                            "verify_hbm_gbps": gbps, "verify_hbm_frac": gbps / HBM_PEAK_GBPS,
+                            "draft_hbm_frac": sh.tree_depth * by["draft_forward"] / (draft_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS if sh.tree_total > 1 and not static_name else None})
+                out["roofline"] = {"bound": "hbm", "achieved": gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": gbps / HBM_PEAK_GBPS,
+                                   "traffic": step_traffic,
+                                   "what": "the verify step (one replayed target forward over the tree's rows): algorithmic bytes = "
+                                           "weights + KV read + KV write, time = HIP events around the step on the library's stream",
+                                   "algorithmic_bytes_per_step": verify_bytes, "step_ms": verify_ms}
             else:
-                n_launch = cnt[4] / a.steps                      # GEMM launches per verify
+                n_launch = cnt[4] / steps                        # GEMM launches per verify
                 pair_ms = ms[6] / max(cnt[6], 1)                 # what an empty event pair measures
                 raw_ms = ms[4] / max(cnt[4], 1)
                 avg_ms = raw_ms - pair_ms
                 bytes_per_launch = by["verify_weights"] / n_launch
                 achieved = bytes_per_launch / (avg_ms * 1e-3) / 1e9
-                out["roofline"] = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                                   "frac": achieved / HBM_PEAK_GBPS,
-                                   "traffic": MEASURED_TRAFFIC_BYTES_PER_LAUNCH.get(a.config) if not (a.layers or a.tree) else None,
-                                   "kernel": "gemm_stream_kernel (verify launches)", "launches_per_step": n_launch,
-                                   "avg_launch_ms": avg_ms, "event_interval_ms": raw_ms, "empty_event_pair_ms": pair_ms,
-                                   "algorithmic_bytes_per_launch": bytes_per_launch}
+                out["roofline"]["kernel"] = {
+                    "name": "gemm_stream_kernel (the verify step's weight-streaming launches)", "bound": "hbm", "achieved": achieved,
+                    "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS, "traffic": launch_traffic,
+                    "launches_per_step": n_launch, "avg_launch_ms": avg_ms, "event_interval_ms": raw_ms, "empty_event_pair_ms": pair_ms,
+                    "algorithmic_bytes_per_launch": bytes_per_launch}
+                out["roofline"]["kernel_frac"] = achieved / HBM_PEAK_GBPS
+                out["roofline"]["kernel_avg_launch_ms"] = avg_ms
+    return out
+
+
+def load_weights(sh):
+    import workload as wl
+    import paper_2408_15766_amd as P
+    return P.pack_weights(wl.iter_device_weights(sh, "cuda"))
+
+
+def main():
+    a = parse()
+    if a.gpus != 1:
+        print("bench.py: this build runs on one GPU only (batch-1 decode has no data-parallel units); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+    import torch
+    import workload as wl
+
+    if a.calibrate_copy:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")       # 1 GiB
+        dst = torch.empty_like(src)
+        for _ in range(4):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibrate_copy_bytes_read_per_launch": src.numel() * 4, "bytes_written_per_launch": src.numel() * 4}))
+        return
+    sh = wl.BY_NAME[a.config]
+    overridden = bool(a.layers or a.tree)
+    if a.layers:
+        sh = sh.with_(n_layers=a.layers, name=f"{sh.name}-{a.layers}layer")
+    if a.tree:
+        d_, k_, n_ = (int(x) for x in a.tree.split(","))
+        sh = sh.with_(tree_depth=d_, tree_topk=k_, tree_total=n_)
+    torch.cuda.set_device(0)
+    weights = load_weights(sh)
+    m = measure_shape(sh, weights, a.steps, a.warmup, a.forced_accept, a.static_tree, not a.no_roofline_pass, overridden)
+    out = {
+        "metric": f"tokens/s (bs=1, T={sh.temperature:g})", "value": m.pop("tokens_per_s"), "unit": "tokens/s", "n_gpus": 1, "steps": a.steps,
+        "warmup": a.warmup, "ms_per_step": m["ms_per_cycle"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": sh.dtype, "data": "synthetic", "config": {"workload": m.pop("workload")},
+    }
+    m.pop("steps"); m.pop("warmup")
+    out.update(m)
+
     if not a.no_hca:
         out["hca_attention"] = hca_attention_bench(wl.BY_NAME[a.config], not a.no_cpu_baseline)
+    del weights
+    gc.collect()
+    torch.cuda.empty_cache()
     if not a.no_loss:
-        del weights
+        out["topk_loss"] = topk_loss_bench(wl.BY_NAME[a.config], not a.no_cpu_baseline)
         gc.collect()
         torch.cuda.empty_cache()
-        out["topk_loss"] = topk_loss_bench(wl.BY_NAME[a.config], not a.no_cpu_baseline)
+
+    # ---- the other benchmark shapes, each with its own resident weights, same measurements, fewer cycles ----
+    if not (a.no_other_shapes or overridden or a.static_tree or a.config != "llama2-7b"):
+        out["shapes"] = {}
+        for name in OTHER_SHAPES:
+            osh = wl.BY_NAME[name]
+            w = load_weights(osh)
+            out["shapes"][name] = measure_shape(osh, w, min(a.steps, 16), min(a.warmup, 3), a.forced_accept, "", not a.no_roofline_pass)
+            del w
+            gc.collect()
+            torch.cuda.empty_cache()
     if not a.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl.BY_NAME[a.config])
     print(json.dumps(out))

@@ -88,6 +88,26 @@ def test_tiny_fp32_tree_shapes_match_oracle(env, tiny_gpu, shape):
         assert np.abs(a["logits"] - b["logits"]).max() < 1e-4
 
 
+def assert_committed_rows_equal_plain(srec, prec):
+    """Every row of a speculative cycle that gets committed (the root and each accepted node) carries, bit for bit, the
+    logits plain decoding produced for the same position: the accepted node of depth d of a cycle that started with n
+    committed tokens sits at position n + d, where plain decoding ran its single row when it had n + d tokens committed."""
+    plain_at = {r["n"]: r["logits"][0] for r in prec}
+    checked = deeper = 0
+    for r in srec:
+        t, cur = r["tree"], 0
+        nodes = [0]
+        for tok in r["emitted"][:-1]:                          # the accepted tokens; the last emitted one is the bonus
+            cur = next(c for c in range(cur + 1, t.n_nodes) if t.parent[c] == cur and t.token[c] == tok)
+            nodes.append(cur)
+        for d, node in enumerate(nodes):
+            if r["n"] + d in plain_at:
+                assert np.array_equal(r["logits"][node], plain_at[r["n"] + d]), (r["n"], d, node)
+                checked += 1
+                deeper += d > 0
+    return checked, deeper
+
+
 def forge_hook(stream, n_prompt, plan, rng, vocab):
     """Graft the known continuation into the GPU-drafted tree (host arrays of the C ABI)."""
     def hook(eng, t):
@@ -297,20 +317,40 @@ def bf16_model(request, env):
     return sh, hw, P.upload_weights(hw, sh.dtype), wl.make_prompt(sh)
 
 
+# Ceilings of the bf16 logit comparisons: a few percent above what the kernels measure on these models (maximum 0.0307 /
+# 0.0309, rms 0.0061 / 0.0063 against the bf16-storage evaluation of the oracle; maximum 0.067 / 0.073, rms 0.0129 /
+# 0.0137, 99.56 .. 99.70 % inside the tolerance against the plain oracle).
+STORE_MAX, STORE_RMS = 0.034, 0.0068
+PLAIN_MAX, PLAIN_RMS, PLAIN_INSIDE = 0.080, 0.0145, 0.995
+
+
+def oracle_logits_for(hw, sh, prompt, t, first, dtype, store):
+    st, _ = oracle.prefill(as_dtype(hw, dtype), sh, prompt, len(prompt) + 200, dtype=dtype, store=store)
+    ot = oracle.Tree(t.token[:t.n_nodes].copy(), t.parent[:t.n_nodes].copy(), t.depth[:t.n_nodes].copy(), t.score[:t.n_nodes].copy())
+    ot.token[0] = first                       # compare on the GPU's root token even if a near-tie flipped the oracle's
+    return np.asarray(oracle.verify_tree(st, ot)[0], dtype=np.float64)
+
+
+def logit_stats(name, x, ref, tag):
+    err = np.abs(x - ref)
+    ok = err <= 3e-2 + 2e-2 * np.abs(ref)
+    print(f"{name} {tag}: max err {err.max():.4f} rms {np.sqrt((err ** 2).mean()):.4f} within tolerance {ok.mean() * 100:.4f} %")
+    return err.max(), np.sqrt((err ** 2).mean()), ok
+
+
 def test_bf16_logits_within_tolerance_of_oracle(env, bf16_model):
     """Real widths, two layers: GPU bf16 logits of a verified tree against the oracle on the same tree.
 
-    Tolerance per logit: 3e-2 + 2e-2 |ref|.
+    Tolerance per logit: 3e-2 + 2e-2 |ref|, required of EVERY logit.
 
-    (1) Against the oracle evaluated with the configuration's storage type (activations, keys and values held in
-        bf16 between operations, fp64 arithmetic).  Any fp32 implementation differs from this reference where an
-        fp32 and an fp64 intermediate fall on different sides of a bf16 rounding boundary; the size of that effect
-        is measured here by evaluating the SAME oracle code in fp32 arithmetic (max ~0.03, rms ~0.006 at these
-        widths).  Required: at least 99.99 % of the logits within tolerance, and max / rms error no larger than
-        2x / 1.5x what the oracle's own fp32 evaluation shows.
-    (2) Against the plain fp32 oracle (no storage rounding): the tolerance holds for at least 99 % of the logits and
-        the error stays within what bf16 storage of the cached keys/values and of the GEMM inputs must produce
-        (rms < 0.02, max < 0.12 at logit sigma 1.3)."""
+    The reference is the oracle evaluated with the configuration's storage type: `store=round_to_bf16` rounds the
+    tensors that a bf16 configuration holds in memory between two operations (norm outputs, cached keys and values,
+    the attention output, the SwiGLU output, the features) and leaves the residual stream, the queries and every
+    accumulation in fp64.  Those are the storage points of this library's kernels, so this reading describes what
+    the kernels are meant to compute; the oracle's default (no rounding anywhere) stays the plain definition.
+    Against that plain definition the tolerance cannot hold for every logit once keys, values and GEMM inputs are
+    bf16 (rounding the cached keys and values alone moves single logits by more than 0.03 at a logit spread of 1.3);
+    that comparison is reported and held to fixed ceilings as a regression guard."""
     torch, P = env
     sh, hw, dw, prompt = bf16_model
     eng = P.Engine(sh, dw)
@@ -318,26 +358,13 @@ def test_bf16_logits_within_tolerance_of_oracle(env, bf16_model):
     t = eng.draft_tree()
     eng.verify(t)
     got = eng.logits(t.n_nodes)
-
-    def oracle_logits(dtype, store):
-        st, _ = oracle.prefill(as_dtype(hw, dtype), sh, prompt, len(prompt) + 200, dtype=dtype, store=store)
-        ot = oracle.Tree(t.token[:t.n_nodes].copy(), t.parent[:t.n_nodes].copy(), t.depth[:t.n_nodes].copy(), t.score[:t.n_nodes].copy())
-        ot.token[0] = first                   # compare on the GPU's root token even if a near-tie flipped the oracle's
-        return np.asarray(oracle.verify_tree(st, ot)[0], dtype=np.float64)
-
-    def stats(x, ref, tag):
-        err = np.abs(x - ref)
-        ok = err <= 3e-2 + 2e-2 * np.abs(ref)
-        print(f"{sh.name} {tag}: max err {err.max():.4f} rms {np.sqrt((err ** 2).mean()):.4f} within tolerance {ok.mean() * 100:.4f} %")
-        return err.max(), np.sqrt((err ** 2).mean()), ok.mean()
-
-    ref_store = oracle_logits(np.float64, wl.round_to_bf16)
-    floor_max, floor_rms, _ = stats(oracle_logits(np.float32, wl.round_to_bf16), ref_store, "oracle fp32 arithmetic vs fp64, bf16 storage")
-    g_max, g_rms, g_ok = stats(got, ref_store, "GPU vs oracle with bf16 storage")
-    assert g_ok >= 0.9999
-    assert g_max <= max(3e-2, 2.0 * floor_max) and g_rms <= max(3e-3, 1.5 * floor_rms)
-    p_max, p_rms, p_ok = stats(got, oracle_logits(np.float32, None), "GPU vs plain fp32 oracle")
-    assert p_ok >= 0.99 and p_max < 0.12 and p_rms < 0.02
+    g_max, g_rms, ok = logit_stats(sh.name, got, oracle_logits_for(hw, sh, prompt, t, first, np.float64, wl.round_to_bf16),
+                                   "GPU vs oracle with bf16 storage")
+    assert ok.all()
+    assert g_max <= STORE_MAX and g_rms <= STORE_RMS
+    p_max, p_rms, p_ok = logit_stats(sh.name, got, oracle_logits_for(hw, sh, prompt, t, first, np.float32, None),
+                                     "GPU vs plain fp32 oracle (informational)")
+    assert p_ok.mean() >= PLAIN_INSIDE and p_max < PLAIN_MAX and p_rms < PLAIN_RMS
 
 
 def test_bf16_prefill_in_several_tiles_matches_oracle(env):
@@ -353,21 +380,31 @@ def test_bf16_prefill_in_several_tiles_matches_oracle(env):
     first = eng.prefill(prompt)
     t = eng.draft_tree()
     eng.verify(t)
-    got = eng.logits(t.n_nodes)
+    g_max, g_rms, ok = logit_stats(sh.name, eng.logits(t.n_nodes), oracle_logits_for(hw, sh, prompt, t, first, np.float64, wl.round_to_bf16),
+                                   "GPU vs oracle with bf16 storage")
+    assert ok.all() and g_max <= STORE_MAX and g_rms <= STORE_RMS
 
-    def oracle_logits(dtype):
-        st, _ = oracle.prefill(as_dtype(hw, dtype), sh, prompt, len(prompt) + 200, dtype=dtype, store=wl.round_to_bf16)
-        ot = oracle.Tree(t.token[:t.n_nodes].copy(), t.parent[:t.n_nodes].copy(), t.depth[:t.n_nodes].copy(), t.score[:t.n_nodes].copy())
-        ot.token[0] = first
-        return np.asarray(oracle.verify_tree(st, ot)[0], dtype=np.float64)
 
-    ref = oracle_logits(np.float64)
-    floor = np.abs(oracle_logits(np.float32) - ref)
-    err = np.abs(got - ref)
-    ok = err <= 3e-2 + 2e-2 * np.abs(ref)
-    print(f"{sh.name}: GPU max err {err.max():.4f} rms {np.sqrt((err ** 2).mean()):.4f}; oracle fp32 max {floor.max():.4f} rms {np.sqrt((floor ** 2).mean()):.4f}")
-    assert ok.mean() >= 0.9999
-    assert err.max() <= max(3e-2, 2.0 * floor.max()) and np.sqrt((err ** 2).mean()) <= max(3e-3, 1.5 * np.sqrt((floor ** 2).mean()))
+LONG_PROMPT = [wl.LLAMA2_7B.with_(name="llama2-7b-2layer-p1400", n_layers=2, prompt_len=1400, gen_tokens=8),
+               wl.LLAMA3_8B.with_(name="llama3-8b-width-2layer-p1400", n_layers=2, vocab=8192, d_ffn=4096, prompt_len=1400, gen_tokens=8)]
+
+
+@pytest.mark.parametrize("sh", LONG_PROMPT, ids=lambda s: s.name)
+def test_bf16_logits_long_prompt_within_tolerance_of_oracle(env, sh):
+    """A 1400-token prompt: every verified row's attention runs eight 128-key parts and the 256-key parts beyond
+    position 1024 on the matrix cores (and the prefill three 512-row chunks), MHA 32 x 128 and GQA 32 / 8; the logits
+    of the verified tree against the bf16-storage oracle, every logit inside the tolerance."""
+    torch, P = env
+    hw = wl.make_weights(sh)
+    dw = P.upload_weights(hw, sh.dtype)
+    prompt = wl.make_prompt(sh)
+    eng = P.Engine(sh, dw)
+    first = eng.prefill(prompt)
+    t = eng.draft_tree()
+    eng.verify(t)
+    g_max, g_rms, ok = logit_stats(sh.name, eng.logits(t.n_nodes), oracle_logits_for(hw, sh, prompt, t, first, np.float64, wl.round_to_bf16),
+                                   "GPU vs oracle with bf16 storage")
+    assert ok.all() and g_max <= STORE_MAX and g_rms <= STORE_RMS
 
 
 def test_bf16_spec_equals_greedy_bit_exact(env, bf16_model):
@@ -387,10 +424,9 @@ def test_bf16_spec_equals_greedy_bit_exact(env, bf16_model):
     srec = []
     got2, taus2 = spec2.generate(prompt, gen, tree_hook=forge_hook(greedy, len(prompt), lambda n: n % 5, rng, sh.vocab), record=srec)
     assert got2 == greedy[:gen] and max(taus2) >= 4
-    # logits of the root row of every cycle == logits plain decoding produced at the same position, bit for bit
-    plain_at = {r["n"]: r["logits"][0] for r in prec}
-    for r in srec:
-        assert np.array_equal(r["logits"][0], plain_at[r["n"]])
+    # logits of every committed row (root and accepted nodes) == logits plain decoding produced at that position
+    checked, deeper = assert_committed_rows_equal_plain(srec, prec)
+    assert checked >= len(srec) and deeper >= 3
 
 
 @pytest.mark.parametrize("shape", [(15, 16, 128), (8, 10, 80), (2, 4, 7)], ids=lambda s: "D%d-K%d-N%d" % s)
@@ -412,9 +448,8 @@ def test_bf16_other_tree_shapes_equal_greedy_bit_exact(env, bf16_model, shape):
     srec = []
     got, taus = spec.generate(prompt, gen, tree_hook=forge_hook(greedy, len(prompt), lambda n: n % (min(D, 6) + 1), rng, sh.vocab), record=srec)
     assert got == greedy[:gen] and max(taus) >= min(D, 3)
-    plain_at = {r["n"]: r["logits"][0] for r in prec}
-    for r in srec:
-        assert np.array_equal(r["logits"][0], plain_at[r["n"]])
+    checked, deeper = assert_committed_rows_equal_plain(srec, prec)
+    assert checked >= len(srec) and deeper >= min(D, 3) - 1
 
 
 def test_graph_replay_equals_eager_launches(env, bf16_model):
@@ -510,9 +545,8 @@ def test_long_context_spec_equals_greedy_bit_exact(env):
     srec = []
     got, taus = spec.generate(prompt, gen, tree_hook=forge_hook(greedy, len(prompt), lambda n: (n * 7) % 6, rng, sh.vocab), record=srec)
     assert got == greedy[:gen] and max(taus) >= 4
-    plain_at = {r["n"]: r["logits"][0] for r in prec}
-    for r in srec:
-        assert np.array_equal(r["logits"][0], plain_at[r["n"]])
+    checked, deeper = assert_committed_rows_equal_plain(srec, prec)
+    assert checked >= len(srec) and deeper >= 3
 
 
 def test_full_depth_7b_bench_configuration(env):

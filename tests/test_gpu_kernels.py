@@ -1,4 +1,6 @@
 """GPU parity of the individual kernels (through the C ABI) against the CPU oracle's functions."""
+import zlib
+
 import numpy as np
 import pytest
 
@@ -14,6 +16,11 @@ def env():
     import paper_2408_15766_amd as P
     assert torch.cuda.is_available()
     return torch, P
+
+
+def case_seed(*case):
+    """A fixed seed per test case (the built-in hash of a tuple with a string in it changes from process to process)."""
+    return zlib.crc32(repr(case).encode())
 
 
 def rand_storage(rng, shape, dtype, scale=1.0):
@@ -49,7 +56,7 @@ GEMM_CASES = [
 @pytest.mark.parametrize("dtype,m,k,rows,n_split", GEMM_CASES)
 def test_gemm_matches_matmul(env, dtype, m, k, rows, n_split):
     torch, P = env
-    rng = np.random.default_rng(hash((dtype, m, k, rows)) % 2**32)
+    rng = np.random.default_rng(case_seed(dtype, m, k, rows))
     x = rand_storage(rng, (m, k), dtype)
     ws = [rand_storage(rng, (r, k), dtype, 0.05) for r in rows]
     part = P.spec_k_gemm(to_dev(torch, x, dtype), [to_dev(torch, w, dtype) for w in ws], n_split)
@@ -91,8 +98,22 @@ def make_tree(rng, rows, max_depth):
     return par, dep, anc
 
 
+def attention_error_ok(got, want, dtype, v_max):
+    """got, want: arrays of the same shape.  fp32 storage: 1e-5.  bf16 storage: keys and values are exact, queries and
+    probabilities enter the matrix cores as bf16 hi + lo pairs (relative 2^-16), sums are fp32, and the output is
+    rounded to bf16 (relative 2^-9 of the element), so per element |err| <= 2^-8 |want| + 2^-12 max|v| and over the
+    whole output rms(err) <= 2^-9 rms(want) + 1e-4.  With outputs of 0.03 .. 0.07 (averages over hundreds of
+    unit-variance values) this is a few 1e-4: a dropped block of keys changes the output by several 1e-3."""
+    err = np.abs(got - want)
+    if dtype == "fp32":
+        return err.max() < 1e-5
+    per_elem = (err <= 2.0 ** -8 * np.abs(want) + 2.0 ** -12 * v_max).all()
+    rms_ok = np.sqrt((err ** 2).mean()) <= 2.0 ** -9 * np.sqrt((want ** 2).mean()) + 1e-4
+    return bool(per_elem and rms_ok)
+
+
 ATTN_CASES = [
-    # dtype, hq, hkv, hd, base, rows, tree?
+    # dtype, hq, hkv, hd, base, rows, tree?, query scale
     ("fp32", 4, 4, 64, 32, 16, True),
     ("fp32", 4, 2, 64, 0, 7, True),
     ("fp32", 8, 1, 128, 65, 16, True),
@@ -105,15 +126,20 @@ ATTN_CASES = [
     ("fp32", 2, 1, 64, 1010, 24, True),         # rows straddle position 1024, where the parts become 256 keys long
     ("fp32", 2, 2, 64, 1500, 8, True),          # several of the longer parts, the last one ragged (vector path)
     ("bf16", 4, 2, 128, 1290, 40, True),        # the same on the matrix-core path
+    ("bf16", 4, 2, 128, 1290, 40, True, 6.0),   # peaked scores: a few keys carry the row, outputs of order one
+    ("bf16", 8, 1, 128, 2600, 12, True),        # 8 query heads per kv head (the 70B head layout), several far parts
+    ("bf16", 2, 2, 64, 1100, 33, True, 6.0),    # head dim 64 on the matrix-core path
 ]
 
 
-@pytest.mark.parametrize("dtype,hq,hkv,hd,base,rows,is_tree", ATTN_CASES)
-def test_attention_matches_oracle(env, dtype, hq, hkv, hd, base, rows, is_tree):
+@pytest.mark.parametrize("case", ATTN_CASES, ids=lambda c: "-".join(str(x) for x in c))
+def test_attention_matches_oracle(env, case):
     torch, P = env
-    rng = np.random.default_rng(hash((dtype, hq, hkv, hd, base, rows)) % 2**32)
+    dtype, hq, hkv, hd, base, rows, is_tree = case[:7]
+    q_scale = case[7] if len(case) > 7 else 1.0
+    rng = np.random.default_rng(case_seed(*case))
     slots = base + rows
-    q = rand_storage(rng, (rows, hq * hd), dtype)
+    q = rand_storage(rng, (rows, hq * hd), dtype, q_scale)
     kc = rand_storage(rng, (slots, hkv * hd), dtype)
     vc = rand_storage(rng, (slots, hkv * hd), dtype)
     if is_tree:
@@ -123,17 +149,16 @@ def test_attention_matches_oracle(env, dtype, hq, hkv, hd, base, rows, is_tree):
     out = P.spec_k_attention(to_dev(torch, q, "fp32"), to_dev(torch, kc, dtype), to_dev(torch, vc, dtype), base,
                              torch.from_numpy(dep).cuda(), None if anc is None else torch.from_numpy(anc).cuda(), hq, hkv, hd)
     torch.cuda.synchronize()
-    got = out.float().cpu().numpy().reshape(rows, hq, hd)
+    got = out.float().cpu().numpy().reshape(rows, hq, hd).astype(np.float64)
     g = hq // hkv
     k3, v3 = kc.reshape(slots, hkv, hd).astype(np.float64), vc.reshape(slots, hkv, hd).astype(np.float64)
     q3 = q.reshape(rows, hq, hd).astype(np.float64)
-    worst = 0.0
+    want = np.zeros_like(got)
     for i in range(rows):
         vis = list(range(base)) + ([base + a for a in anc[i, :dep[i] + 1]] if is_tree else list(range(base, base + i + 1)))
         for h in range(hq):
-            want = attention_row(q3[i, h], k3[vis, h // g], v3[vis, h // g])
-            worst = max(worst, np.abs(got[i, h] - want).max())
-    assert worst < (1e-5 if dtype == "fp32" else 2e-2)
+            want[i, h] = attention_row(q3[i, h], k3[vis, h // g], v3[vis, h // g])
+    assert attention_error_ok(got, want, dtype, np.abs(vc).max())
 
 
 def test_attention_tree_row_equals_compacted_chain_row(env):
@@ -191,22 +216,26 @@ def test_gemm_large_shapes_sampled_against_oracle(env, name, rows, k, n_split):
         assert np.abs(got[:, c] - want).max() < 2e-3
 
 
-def test_attention_long_context_matches_oracle(env):
-    """Long-KV verify of the LLaMA3-8B configuration: 4100 cached keys, GQA 4:1, sampled rows and heads."""
+@pytest.mark.parametrize("q_scale", [1.0, 6.0], ids=["flat", "peaked"])
+def test_attention_long_context_matches_oracle(env, q_scale):
+    """Long-KV verify of the LLaMA3-8B configuration: 4100 cached keys (eight 128-key parts and thirteen 256-key parts
+    on the matrix cores), GQA 4:1, sampled rows and heads; near-uniform and peaked score distributions."""
     torch, P = env
     rng = np.random.default_rng(77)
     hq, hkv, hd, base, rows = 8, 2, 128, 4100, 60
     par, dep, anc = make_tree(rng, rows, 6)
-    q = rand_storage(rng, (rows, hq * hd), "bf16")
+    q = rand_storage(rng, (rows, hq * hd), "bf16", q_scale)
     kc = rand_storage(rng, (base + rows, hkv * hd), "bf16")
     vc = rand_storage(rng, (base + rows, hkv * hd), "bf16")
     out = P.spec_k_attention(to_dev(torch, q, "fp32"), to_dev(torch, kc, "bf16"), to_dev(torch, vc, "bf16"), base,
                              torch.from_numpy(dep).cuda(), torch.from_numpy(anc).cuda(), hq, hkv, hd)
-    got = out.float().cpu().numpy().reshape(rows, hq, hd)
+    got_all = out.float().cpu().numpy().reshape(rows, hq, hd).astype(np.float64)
     k3, v3 = kc.reshape(-1, hkv, hd).astype(np.float64), vc.reshape(-1, hkv, hd).astype(np.float64)
     q3 = q.reshape(rows, hq, hd).astype(np.float64)
-    for i in (0, 1, 17, 59):
+    got, want = [], []
+    for i in (0, 1, 17, 40, 59):
         vis = list(range(base)) + [base + a for a in anc[i, :dep[i] + 1]]
-        for h in (0, 3, 7):
-            want = attention_row(q3[i, h], k3[vis, h // 4], v3[vis, h // 4])
-            assert np.abs(got[i, h] - want).max() < 2e-2
+        for h in (0, 3, 4, 7):
+            want.append(attention_row(q3[i, h], k3[vis, h // 4], v3[vis, h // 4]))
+            got.append(got_all[i, h])
+    assert attention_error_ok(np.array(got), np.array(want), "bf16", np.abs(vc).max())
