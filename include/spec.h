@@ -118,11 +118,23 @@ uint64_t spec_workspace_bytes(const spec_config *cfg);
 /* State machine: create -> CREATED; prefill -> READY; draft_tree -> DRAFTED;
  * verify -> VERIFIED; accept -> READY.  Other orders return SPEC_ESTATE. */
 
-/* Validates the configuration, carves the workspace, keeps copies of cfg and
- * of the weight pointer table.  *out receives the context. */
+/* Sets up the two models the method runs (Sec. 2: a target LLM and a draft
+ * model that takes the target's last hidden state together with the token
+ * embedding and shares the target's embedding and LM head; Sec. 4.1: LLaMA
+ * targets, tree of `tree_depth` / `tree_total`).  Validates the configuration,
+ * carves the workspace, keeps copies of cfg and of the weight pointer table.
+ * *out receives the context.  Errors: SPEC_EINVAL (bad configuration, NULL
+ * weight pointer, workspace NULL or misaligned), SPEC_ECAP (workspace too
+ * small), SPEC_EHIP; the message is in spec_last_error(NULL). */
 int spec_create(const spec_config *cfg, const spec_weights *w, spec_ctx **out);
 
-/* Runs the target over the prompt (HOST int32 array, 1 <= n_prompt, n_prompt +
+/* Produces the state speculation starts from (Sec. 2: drafting begins at a
+ * given timestep t and needs the target's hidden state of step t-1 and the
+ * token of step t): the target runs over the prompt, which yields its feature
+ * at the last position and the first generated token, and the draft model runs
+ * over the prompt's (feature of position i-1, token i) pairs so that its own
+ * cache covers the context.
+ * Runs the target over the prompt (HOST int32 array, 1 <= n_prompt, n_prompt +
  * tree_total <= max_seq), fills both KV caches, and chooses the first token
  * from the last row (argmax at T = 0, a sample at T > 0).  That token is
  * returned in *first_token (HOST) and becomes the pending root. */
