@@ -84,6 +84,8 @@ lib.spec_packed_bytes.argtypes = [C.c_int32, C.c_int32, C.c_int32]
 lib.spec_pack_weight.argtypes = [C.c_int32, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
 lib.spec_k_gemm.argtypes = [C.c_int32, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_int32, C.c_void_p,
                             C.c_int32, C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p]
+lib.spec_k_gemm_swiglu.argtypes = [C.c_int32, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p,
+                                   C.c_void_p]
 lib.spec_k_attention.argtypes = [C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
                                  C.c_int32, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p]
 lib.spec_k_topk_logprob.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
@@ -260,6 +262,21 @@ def spec_k_gemm(x, ws: Sequence, n_split: int, m: Optional[int] = None):
     if rc:
         raise SpecError(rc, "spec_k_gemm")
     return part
+
+
+def spec_k_gemm_swiglu(x, w_gate, w_up, packed=None):
+    """x: torch [m, in]; w_gate, w_up: row-major torch [rows, in] (packed here, per call: test use) -> act [m, rows].
+    packed: optional (packed gate, packed up) from an earlier call, to keep packing out of a timed loop."""
+    import torch
+    dtype = 1 if x.dtype == torch.bfloat16 else 0
+    pg, pu = packed if packed is not None else (spec_pack_weight(w_gate.contiguous()), spec_pack_weight(w_up.contiguous()))
+    rows = pg.logical_shape[0]
+    act = torch.full((x.shape[0], rows), float("nan"), dtype=x.dtype, device=x.device)
+    rc = lib.spec_k_gemm_swiglu(dtype, x.data_ptr(), x.stride(0), x.shape[0], x.shape[1], pg.data_ptr(), pu.data_ptr(), rows,
+                                act.data_ptr(), _stream_ptr())
+    if rc:
+        raise SpecError(rc, "spec_k_gemm_swiglu")
+    return act
 
 
 def spec_k_attention(q, kcache, vcache, base: int, depth, anc, hq: int, hkv: int, hd: int):

@@ -1029,6 +1029,26 @@ int spec_k_gemm(int32_t dtype, const void *x, int32_t ldx, int32_t m, int32_t in
   return launch_gemm(dtype, a, (hipStream_t)stream) == hipSuccess ? SPEC_OK : SPEC_EHIP;
 }
 
+int spec_k_gemm_swiglu(int32_t dtype, const void *x, int32_t ldx, int32_t m, int32_t in, const void *w_gate, const void *w_up,
+                       int32_t rows, void *act, void *stream) {
+  if (!x || !w_gate || !w_up || !act || rows < 1 || (dtype != 0 && dtype != 1)) return SPEC_EINVAL;
+  const int epl = dtype == 1 ? 8 : 4;
+  if (in < 1 || in % epl || ldx % epl || m < 1 || m > 4096) return SPEC_EINVAL;
+  GemmArgs a{};
+  a.x = x; a.ldx = ldx; a.m = m; a.in = in;
+  const void *ws[3] = {w_gate, w_up, w_gate};
+  for (int s = 0; s < 3; s++) {
+    a.seg_w[s] = ws[s];
+    a.seg_rows[s] = s < 2 ? rows : 0;
+    a.seg_blocks[s] = s < 2 ? (rows + 31) / 32 : 0;
+    a.seg_col0[s] = s * rows;
+  }
+  a.nseg = 2; a.total_blocks = 2 * a.seg_blocks[0];
+  a.part = nullptr; a.ldp = 2 * rows; a.m_pad = m; a.n_split = 1;
+  a.act = act;
+  return launch_gemm(dtype, a, (hipStream_t)stream) == hipSuccess ? SPEC_OK : SPEC_EHIP;
+}
+
 int spec_k_attention(int32_t dtype, const void *q, const void *kcache, const void *vcache, int32_t rows, int32_t hq,
                      int32_t hkv, int32_t hd, int32_t base, const int32_t *depth, const int32_t *anc, int32_t max_depth,
                      float *scratch, int32_t max_parts, void *out, void *stream) {

@@ -293,6 +293,7 @@ __global__ __launch_bounds__(64) void attn_part_kernel(AttnArgs a) {
 // parts are fetched by one thread each and turned into weights in LDS, so that the per-dim pass issues
 // independent, coalesced loads; the sums themselves run in ascending part order.
 constexpr int kCombineChunk = 64;
+constexpr int kCombineFew = 8;         // up to this many parts a thread keeps everything in registers
 template <typename T, int HD>
 __global__ __launch_bounds__(HD) void attn_combine_kernel(AttnArgs a) {
   __shared__ float pm[kCombineChunk], pl[kCombineChunk];
@@ -303,6 +304,28 @@ __global__ __launch_bounds__(HD) void attn_combine_kernel(AttnArgs a) {
   const int n_parts = n_front + (a.tail_only ? 1 : 0);
   const float *src = a.part + ((size_t)i * a.hq + h) * a.max_parts * (HD + 2);
   auto slot = [&](int t) { return (size_t)(t < n_front ? t : a.max_parts - 1) * (HD + 2); };
+  if (n_parts <= kCombineFew) {
+    // Few parts (short contexts): every value is requested up front (clamped to a valid part; absent ones are not used),
+    // then the same arithmetic as below runs out of registers: one memory round trip instead of three.
+    float pm_[kCombineFew], pl_[kCombineFew], pv_[kCombineFew];
+#pragma unroll
+    for (int t = 0; t < kCombineFew; t++) {
+      const float *sp = src + slot(t < n_parts ? t : 0);
+      pm_[t] = sp[0]; pl_[t] = sp[1]; pv_[t] = sp[2 + d];
+    }
+    float m = -INFINITY;
+#pragma unroll
+    for (int t = 0; t < kCombineFew; t++) if (t < n_parts) m = fmaxf(m, pm_[t]);
+    float l = 0.f, o = 0.f;
+#pragma unroll
+    for (int t = 0; t < kCombineFew; t++)
+      if (t < n_parts) {
+        const float w = __expf(pm_[t] - m);
+        l += pl_[t] * w; o += pv_[t] * w;
+      }
+    ((T *)a.out)[((size_t)i * a.hq + h) * HD + d] = from_f32<T>(o / l);
+    return;
+  }
   // pass 1: the row's maximum
   float m = -INFINITY;
   for (int t = d; t < n_parts; t += HD) m = fmaxf(m, src[slot(t)]);

@@ -27,6 +27,14 @@ template <typename T> __device__ __forceinline__ T from_f32(float x);
 template <> __device__ __forceinline__ float from_f32<float>(float x) { return x; }
 template <> __device__ __forceinline__ bf16_t from_f32<bf16_t>(float x) { bf16_t r; r.v = f32_to_bf16_bits(x); return r; }
 
+// SwiGLU of one (gate, up) pair: silu(g) * u with silu(g) = g / (1 + e^-g), through the hardware's exp2 and reciprocal
+// (about 1 ulp each; the result is rounded to the storage type afterwards).  Every kernel that forms the activation
+// uses this one expression.
+__device__ __forceinline__ float silu_mul(float g, float u) {
+  const float e = __builtin_amdgcn_exp2f(g * -1.4426950408889634f);      // e^-g; large |g|: 0 or +inf, both give the right limit
+  return g * __builtin_amdgcn_rcpf(1.0f + e) * u;
+}
+
 // Rotary embedding of the plane (a, b) = (dim j, dim j + hd/2) by (cos, sin).  Contraction into fused multiply-adds is
 // switched off here: which product the compiler would fuse depends on the surrounding code, and every kernel that
 // rotates the same inputs has to get the same bits.

@@ -224,27 +224,34 @@ __global__ __launch_bounds__(kGemmThreads, (TB <= 2 && kStages <= 3) ? 2 : 1) vo
   for (; s < n_slab; s += kPeriod) period(std::false_type{}, s);
 
   if (swiglu) {
-    // the up waves hand their tiles to the gate waves through LDS (the X slabs are no longer needed)
-    float *xch = (float *)lds;                                // [half_waves][64 lanes][TB*16]
+    // Gate wave w and up wave w + half_waves hold the same (columns, tokens).  Each finishes half of the values: the
+    // gate wave the accumulator entries v < 8, the up wave v >= 8, after the two have swapped the halves the other needs
+    // through LDS (the X slabs are no longer needed; value-major, lane-minor layout: no bank conflicts).
+    float *xch = (float *)lds;                                // [wave][TB * 8 values][64 lanes]
+    const bool is_up = wave >= half_waves;
+    const int v_mine = is_up ? 8 : 0, v_theirs = is_up ? 0 : 8;
     __syncthreads();
-    if (wave >= half_waves) {
-      float *dst = xch + ((size_t)(wave - half_waves) * 64 + lane) * (TB * 16);
+    {
+      float *dst = xch + (size_t)wave * (TB * 8 * 64) + lane;
 #pragma unroll
       for (int t = 0; t < TB; t++)
 #pragma unroll
-        for (int v = 0; v < 16; v++) dst[t * 16 + v] = acc[t][v];
+        for (int v = 0; v < 8; v++) dst[(t * 8 + v) * 64] = is_up ? acc[t][v] : acc[t][8 + v];   // what the partner finishes
     }
     __syncthreads();
-    if (wave >= half_waves || !active || row >= seg_rows) return;
-    const float *src = xch + ((size_t)wave * 64 + lane) * (TB * 16);
+    if (!active || row >= seg_rows) return;
+    const float *src = xch + (size_t)(is_up ? wave - half_waves : wave + half_waves) * (TB * 8 * 64) + lane;
     T *act = (T *)a.act + (size_t)mt * 128 * seg_rows + row;
+    (void)v_theirs;
 #pragma unroll
     for (int t = 0; t < TB; t++)
 #pragma unroll
-      for (int v = 0; v < 16; v++) {
+      for (int v8 = 0; v8 < 8; v8++) {
+        const int v = v_mine + v8;
         const int i = t * 32 + 8 * (v >> 2) + 4 * g + (v & 3);
-        const float gv = acc[t][v], uv = src[t * 16 + v];
-        if (i < m_loc) act[(size_t)i * seg_rows] = from_f32<T>(gv / (1.0f + expf(-gv)) * uv);
+        const float mine = is_up ? acc[t][8 + v8] : acc[t][v8], other = src[(t * 8 + v8) * 64];
+        const float gv = is_up ? other : mine, uv = is_up ? mine : other;
+        if (i < m_loc) act[(size_t)i * seg_rows] = from_f32<T>(silu_mul(gv, uv));
       }
     return;
   }
@@ -404,7 +411,7 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_tiled_kernel(GemmArgs a)
       for (int v = 0; v < 16; v++) {
         const int i = t * 32 + 8 * (v >> 2) + 4 * g + (v & 3);
         const float gv = acc[0][t][v], uv = acc[1][t][v];
-        if (i < m_loc) act[(size_t)i * seg_rows[0]] = from_f32<T>(gv / (1.0f + expf(-gv)) * uv);
+        if (i < m_loc) act[(size_t)i * seg_rows[0]] = from_f32<T>(silu_mul(gv, uv));
       }
     return;
   }

@@ -58,6 +58,13 @@ template <> __device__ __forceinline__ void store4<bf16_t>(bf16_t *p, f32x4_t v)
 template <typename T, int PER>
 __device__ __forceinline__ void finish_row(f32x4_t (&v)[PER], int d, const T *norm_w, float eps, float *h_row, T *x_row,
                                            float *sh) {
+  // the norm weights are requested before the row-wide reduction, so that their latency hides behind it
+  f32x4_t nw[PER];
+#pragma unroll
+  for (int e = 0; e < PER; e++) {
+    const int c = (e * kNormThreads + threadIdx.x) * 4;
+    nw[e] = (norm_w != nullptr && c < d) ? load4<T>(norm_w + c) : f32x4_t{1.f, 1.f, 1.f, 1.f};
+  }
   float ss = 0.f;
 #pragma unroll
   for (int e = 0; e < PER; e++) {
@@ -74,7 +81,7 @@ __device__ __forceinline__ void finish_row(f32x4_t (&v)[PER], int d, const T *no
     const int c = (e * kNormThreads + threadIdx.x) * 4;
     if (c < d) {
       f32x4_t o = v[e];
-      if (norm_w != nullptr) o = o * r * load4<T>(norm_w + c);
+      if (norm_w != nullptr) o = o * r * nw[e];
       store4<T>(x_row + c, o);
     }
   }
@@ -217,25 +224,38 @@ __global__ void reduce_rope_kv_kernel(const float *part, int n_split, int m_pad,
                                       const float2 *rope, const int *slot, float *q, T *kcache, T *vcache) {
   const int i = blockIdx.x, head = blockIdx.y, j = threadIdx.x, half = hd >> 1;
   const int col = head * hd + j;                       // q heads, then k heads, then v heads: the GEMM's column order
-  float a = part[(size_t)i * ldp + col], b = part[(size_t)i * ldp + col + half];
-  for (int s = 1; s < n_split; s++) {
+  // every load is issued before anything is used: partial sums, the row's cache slot, the rotation
+  const int sl = slot[i];
+  const float2 cs = head < hq + hkv ? rope[i * half + j] : make_float2(1.f, 0.f);
+  float pa[8], pb[8];                                  // (clamped to a valid split; absent splits add exactly zero)
+#pragma unroll
+  for (int s = 0; s < 8; s++) {
+    const size_t o = ((size_t)(s < n_split ? s : 0) * m_pad + i) * ldp + col;
+    pa[s] = part[o]; pb[s] = part[o + half];
+  }
+  float a = pa[0], b = pb[0];
+#pragma unroll
+  for (int s = 1; s < 8; s++) {
+    const float k = s < n_split ? 1.f : 0.f;
+    a += pa[s] * k; b += pb[s] * k;
+  }
+  for (int s = 8; s < n_split; s++) {
     a += part[((size_t)s * m_pad + i) * ldp + col];
     b += part[((size_t)s * m_pad + i) * ldp + col + half];
   }
   if (head >= hq + hkv) {                              // value head: stored as is
-    T *dst = vcache + ((size_t)slot[i] * hkv + (head - hq - hkv)) * hd;
+    T *dst = vcache + ((size_t)sl * hkv + (head - hq - hkv)) * hd;
     dst[j] = from_f32<T>(a);
     dst[j + half] = from_f32<T>(b);
     return;
   }
-  const float2 cs = rope[i * half + j];
   const float ra = rope_first(a, b, cs), rb = rope_second(a, b, cs);
   if (head < hq) {                                     // query head: kept in fp32, it is read once and never cached
     float *dst = q + ((size_t)i * hq + head) * hd;
     dst[j] = ra;
     dst[j + half] = rb;
   } else {
-    T *dst = kcache + ((size_t)slot[i] * hkv + (head - hq)) * hd;
+    T *dst = kcache + ((size_t)sl * hkv + (head - hq)) * hd;
     dst[j] = from_f32<T>(ra);
     dst[j + half] = from_f32<T>(rb);
   }
@@ -267,7 +287,7 @@ __global__ __launch_bounds__(kRowThreads) void reduce_swiglu_kernel(const float 
     g += part[((size_t)s * m_pad + i) * ldp + c];
     u += part[((size_t)s * m_pad + i) * ldp + f + c];
   }
-  act[(size_t)i * f + c] = from_f32<T>(g / (1.0f + expf(-g)) * u);
+  act[(size_t)i * f + c] = from_f32<T>(silu_mul(g, u));
 }
 
 hipError_t launch_reduce_swiglu(int dtype, const float *part, int n_split, int m_pad, int ldp, int rows, int f, void *act,

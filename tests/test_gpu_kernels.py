@@ -68,6 +68,25 @@ def test_gemm_matches_matmul(env, dtype, m, k, rows, n_split):
     assert np.abs(got - want).max() < tol
 
 
+@pytest.mark.parametrize("dtype,m,k,rows", [("fp32", 16, 256, 688), ("bf16", 60, 4096, 1100), ("bf16", 1, 1280, 64), ("bf16", 200, 768, 300)])
+def test_gemm_swiglu_epilogue_matches_oracle(env, dtype, m, k, rows):
+    """Gate and up projections with SwiGLU applied inside the launch: silu(x.wg) * (x.wu) against fp64, ragged 32-row
+    blocks, one row, and two 128-row tiles (the prefill form).  bf16 storage rounds the result once (relative 2^-9)."""
+    torch, P = env
+    rng = np.random.default_rng(case_seed("swiglu", dtype, m, k, rows))
+    x = rand_storage(rng, (m, k), dtype)
+    wg, wu = rand_storage(rng, (rows, k), dtype, 0.05), rand_storage(rng, (rows, k), dtype, 0.05)
+    act = P.spec_k_gemm_swiglu(to_dev(torch, x, dtype), to_dev(torch, wg, dtype), to_dev(torch, wu, dtype))
+    torch.cuda.synchronize()
+    got = act.float().cpu().numpy().astype(np.float64)
+    g = x.astype(np.float64) @ wg.astype(np.float64).T
+    u = x.astype(np.float64) @ wu.astype(np.float64).T
+    want = g / (1.0 + np.exp(-g)) * u
+    assert not np.isnan(got).any()
+    tol = 1e-5 * np.sqrt(k) + (2.0 ** -8 * np.abs(want) if dtype == "bf16" else 0.0)
+    assert (np.abs(got - want) <= tol).all()
+
+
 def test_gemm_row_is_independent_of_batch(env):
     """A row computed alone (plain decoding) is bit-identical to the same row inside a 60-row tree."""
     torch, P = env
