@@ -397,8 +397,9 @@ int lm_head(spec_ctx *c, const void *x, int rows, float *logits) {
 // sizes: the launch sequence is then independent of the cycle and can be captured into a graph.
 int target_forward(spec_ctx *c, int m, int base, const RowTables &rt, int max_pos, const int *base_ptr = nullptr) {
   const spec_config &g = c->cfg;
-  HIPCHK(c, launch_rope_table(rt.pos, m, g.head_dim, g.rope_theta, c->rope, c->stream));
-  HIPCHK(c, launch_embed_norm(g.dtype, c->w.embed, rt.token, m, g.d_model, c->layers[0].attn_norm, g.rms_eps, c->h, c->x, c->stream));
+  // (the launch that opens the forward also fills the rotary table of its rows)
+  HIPCHK(c, launch_embed_norm(g.dtype, c->w.embed, rt.token, m, g.d_model, c->layers[0].attn_norm, g.rms_eps, c->h, c->x, c->stream,
+                              rt.pos, g.head_dim, g.rope_theta, c->rope));
   for (int l = 0; l < g.n_layers; l++) {
     char *kc = c->kv_t + (size_t)l * c->t_layer_stride * c->esz;
     char *vc = kc + c->t_kv_stride * c->esz;
@@ -415,8 +416,8 @@ int draft_forward(spec_ctx *c, int m, int base, const void *feat, const int *src
                   const int *base_ptr = nullptr) {
   const spec_config &g = c->cfg;
   const int d = g.d_model;
-  HIPCHK(c, launch_rope_table(rt.pos, m, g.head_dim, g.rope_theta, c->rope, c->stream));
-  HIPCHK(c, launch_concat_feat_embed(g.dtype, feat, src_row, c->w.embed, rt.token, m, d, c->xcat, c->stream));
+  HIPCHK(c, launch_concat_feat_embed(g.dtype, feat, src_row, c->w.embed, rt.token, m, d, c->xcat, c->stream, rt.pos, g.head_dim,
+                                     g.rope_theta, c->rope));
   const Seg segs[1] = {{c->w.draft_fc, d}};
   const GemmPlan p = plan_gemm(d, 2 * d, g.dtype);
   int rc = run_gemm(c, c->xcat, 2 * d, m, 2 * d, segs, 1, c->part, d, c->m_max, p);

@@ -60,14 +60,16 @@ size_t packed_weight_bytes(int dtype, int rows, int in);
 hipError_t launch_pack_weight(int dtype, const void *src, int rows, int in, void *dst, hipStream_t st);
 
 // ---- rowops.hip ------------------------------------------------------------------------------
-// cos/sin of pos[i] * theta^(-2j/hd) for j < hd/2, angles formed in double precision.
-hipError_t launch_rope_table(const int *pos, int rows, int head_dim, float theta, float2 *table, hipStream_t st);
 // h[i] = embed[token[i]] (fp32);  x[i] = rmsnorm(h[i]) * w  in the storage type.
+// With `table` set, the launch also fills the rotary table of its rows: (cos, sin) of pos[i] * theta^(-2j/hd) for j < hd/2,
+// the angles formed in double precision.
 hipError_t launch_embed_norm(int dtype, const void *embed, const int *token, int rows, int d, const void *norm_w,
-                             float eps, float *h, void *x, hipStream_t st);
+                             float eps, float *h, void *x, hipStream_t st, const int *pos = nullptr, int head_dim = 0,
+                             float theta = 0.f, float2 *table = nullptr);
 // xcat[i] = [feat[src_row[i]] ; embed[token[i]]]  ([rows, 2d], storage type).  src_row == nullptr: identity.
 hipError_t launch_concat_feat_embed(int dtype, const void *feat, const int *src_row, const void *embed,
-                                    const int *token, int rows, int d, void *xcat, hipStream_t st);
+                                    const int *token, int rows, int d, void *xcat, hipStream_t st, const int *pos = nullptr,
+                                    int head_dim = 0, float theta = 0.f, float2 *table = nullptr);
 // h[i] = (residual ? h[i] : 0) + sum_s part[s][i][:d];  x[i] = norm_w ? rmsnorm(h[i]) * norm_w : h[i].
 hipError_t launch_reduce_add_norm(int dtype, const float *part, int n_split, int m_pad, int ldp, int rows, int d,
                                   int residual, const void *norm_w, float eps, float *h, void *x, hipStream_t st);

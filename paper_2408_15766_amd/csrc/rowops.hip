@@ -14,23 +14,22 @@ namespace spec {
 constexpr int kRowThreads = 256;      // threads of the elementwise kernels
 constexpr int kNormThreads = 1024;    // threads of the kernels that hold one row per workgroup
 
-// ---- rotary table ------------------------------------------------------------------------
-__global__ void rope_table_kernel(const int *pos, int rows, int half, double log2_theta, float2 *table) {
-  const int i = blockIdx.x, j = threadIdx.x;
-  if (i >= rows || j >= half) return;
-  // angle = pos * theta^(-j/half), formed in double so that large positions keep their phase
+// ---- rotary table: cos/sin of pos[i] * theta^(-2j/hd) for j < hd/2 ------------------------
+// (cos, sin) of pos * theta^(-j/half), the angle formed in double so that large positions keep their phase
+__device__ __forceinline__ float2 rope_entry(int pos, int j, int half, double log2_theta) {
   const double inv = exp2(-(double)j / (double)half * log2_theta);
-  const double ang = (double)pos[i] * inv;
+  const double ang = (double)pos * inv;
   double s, c;
   sincos(ang, &s, &c);
-  table[i * half + j] = make_float2((float)c, (float)s);
+  return make_float2((float)c, (float)s);
 }
-
-hipError_t launch_rope_table(const int *pos, int rows, int head_dim, float theta, float2 *table, hipStream_t st) {
-  if (rows < 1 || head_dim < 2 || head_dim > 512) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(rope_table_kernel, dim3(rows), dim3(head_dim / 2), 0, st, pos, rows, head_dim / 2,
-                     log2((double)theta), table);
-  return hipGetLastError();
+// The kernels that open a forward (one workgroup per row) also fill the row's part of the rotary table, which saves a launch.
+struct RopeFill { const int *pos; int half; double log2_theta; float2 *table; };   // table == nullptr: nothing to fill
+__device__ __forceinline__ void rope_fill_row(const RopeFill &r, int i) {
+  if (r.table != nullptr && (int)threadIdx.x < r.half) r.table[i * r.half + threadIdx.x] = rope_entry(r.pos[i], threadIdx.x, r.half, r.log2_theta);
+}
+static RopeFill make_rope_fill(const int *pos, int head_dim, float theta, float2 *table) {
+  return RopeFill{pos, head_dim / 2, log2((double)theta), table};
 }
 
 // ---- row kernels that end in an RMSNorm: one workgroup per row, the whole row held in registers ----
@@ -89,9 +88,10 @@ __device__ __forceinline__ void finish_row(f32x4_t (&v)[PER], int d, const T *no
 
 template <typename T, int PER>
 __global__ __launch_bounds__(kNormThreads) void embed_norm_kernel(const T *embed, const int *token, int d, const T *norm_w,
-                                                                 float eps, float *h, T *x) {
+                                                                 float eps, float *h, T *x, RopeFill rf) {
   __shared__ float sh[16];
   const int i = blockIdx.x;
+  rope_fill_row(rf, i);
   const T *src = embed + (size_t)token[i] * d;
   f32x4_t v[PER];
 #pragma unroll
@@ -104,23 +104,25 @@ __global__ __launch_bounds__(kNormThreads) void embed_norm_kernel(const T *embed
 
 template <typename T, int PER>
 static void embed_norm_launch(const void *embed, const int *token, int rows, int d, const void *norm_w, float eps, float *h,
-                              void *x, hipStream_t st) {
+                              void *x, const RopeFill &rf, hipStream_t st) {
   hipLaunchKernelGGL((embed_norm_kernel<T, PER>), dim3(rows), dim3(kNormThreads), 0, st, (const T *)embed, token, d,
-                     (const T *)norm_w, eps, h, (T *)x);
+                     (const T *)norm_w, eps, h, (T *)x, rf);
 }
 
 hipError_t launch_embed_norm(int dtype, const void *embed, const int *token, int rows, int d, const void *norm_w,
-                             float eps, float *h, void *x, hipStream_t st) {
-  if (rows < 1 || d < 4 || d % 4 || d > kNormThreads * 4 * 4) return hipErrorInvalidValue;
+                             float eps, float *h, void *x, hipStream_t st, const int *pos, int head_dim, float theta, float2 *table) {
+  if (rows < 1 || d < 4 || d % 4 || d > kNormThreads * 4 * 4 || (table != nullptr && (head_dim < 2 || head_dim / 2 > kNormThreads)))
+    return hipErrorInvalidValue;
+  const RopeFill rf = make_rope_fill(pos, head_dim, theta, table);
   const int per = (d + kNormThreads * 4 - 1) / (kNormThreads * 4);
   if (dtype == 1) {
-    if (per <= 1) embed_norm_launch<bf16_t, 1>(embed, token, rows, d, norm_w, eps, h, x, st);
-    else if (per <= 2) embed_norm_launch<bf16_t, 2>(embed, token, rows, d, norm_w, eps, h, x, st);
-    else embed_norm_launch<bf16_t, 4>(embed, token, rows, d, norm_w, eps, h, x, st);
+    if (per <= 1) embed_norm_launch<bf16_t, 1>(embed, token, rows, d, norm_w, eps, h, x, rf, st);
+    else if (per <= 2) embed_norm_launch<bf16_t, 2>(embed, token, rows, d, norm_w, eps, h, x, rf, st);
+    else embed_norm_launch<bf16_t, 4>(embed, token, rows, d, norm_w, eps, h, x, rf, st);
   } else {
-    if (per <= 1) embed_norm_launch<float, 1>(embed, token, rows, d, norm_w, eps, h, x, st);
-    else if (per <= 2) embed_norm_launch<float, 2>(embed, token, rows, d, norm_w, eps, h, x, st);
-    else embed_norm_launch<float, 4>(embed, token, rows, d, norm_w, eps, h, x, st);
+    if (per <= 1) embed_norm_launch<float, 1>(embed, token, rows, d, norm_w, eps, h, x, rf, st);
+    else if (per <= 2) embed_norm_launch<float, 2>(embed, token, rows, d, norm_w, eps, h, x, rf, st);
+    else embed_norm_launch<float, 4>(embed, token, rows, d, norm_w, eps, h, x, rf, st);
   }
   return hipGetLastError();
 }
@@ -128,10 +130,11 @@ hipError_t launch_embed_norm(int dtype, const void *embed, const int *token, int
 // One workgroup per row; 16-byte pieces, all loads of a thread issued before its stores.
 template <typename T>
 __global__ __launch_bounds__(kRowThreads) void concat_feat_embed_kernel(const T *feat, const int *src_row, const T *embed,
-                                                                        const int *token, int d, T *xcat) {
+                                                                        const int *token, int d, T *xcat, RopeFill rf) {
   typedef __attribute__((ext_vector_type(4))) uint32_t piece_t;
   constexpr int MAXP = 4;                                   // pieces per thread and half handled per pass
   const int i = blockIdx.x;
+  rope_fill_row(rf, i);
   const piece_t *f = (const piece_t *)(feat + (size_t)(src_row ? src_row[i] : i) * d);
   const piece_t *e = (const piece_t *)(embed + (size_t)token[i] * d);
   piece_t *o = (piece_t *)(xcat + (size_t)i * 2 * d);
@@ -152,14 +155,16 @@ __global__ __launch_bounds__(kRowThreads) void concat_feat_embed_kernel(const T 
 }
 
 hipError_t launch_concat_feat_embed(int dtype, const void *feat, const int *src_row, const void *embed,
-                                    const int *token, int rows, int d, void *xcat, hipStream_t st) {
-  if (rows < 1) return hipErrorInvalidValue;
+                                    const int *token, int rows, int d, void *xcat, hipStream_t st, const int *pos, int head_dim, float theta,
+                                    float2 *table) {
+  if (rows < 1 || (table != nullptr && (head_dim < 2 || head_dim / 2 > kRowThreads))) return hipErrorInvalidValue;
+  const RopeFill rf = make_rope_fill(pos, head_dim, theta, table);
   if (dtype == 1)
     hipLaunchKernelGGL(concat_feat_embed_kernel<bf16_t>, dim3(rows), dim3(kRowThreads), 0, st, (const bf16_t *)feat, src_row,
-                       (const bf16_t *)embed, token, d, (bf16_t *)xcat);
+                       (const bf16_t *)embed, token, d, (bf16_t *)xcat, rf);
   else
     hipLaunchKernelGGL(concat_feat_embed_kernel<float>, dim3(rows), dim3(kRowThreads), 0, st, (const float *)feat, src_row,
-                       (const float *)embed, token, d, (float *)xcat);
+                       (const float *)embed, token, d, (float *)xcat, rf);
   return hipGetLastError();
 }
 
