@@ -181,3 +181,66 @@ def test_full_depth_70b_bench_configuration(env):
     for v, w_row in head_rows.items():
         want = r["feats"].astype(np.float64) @ w_row.astype(np.float64)
         assert np.abs(r["logits"][:, v] - want).max() < 4e-3
+
+
+def test_full_depth_8b_bench_configuration(env):
+    """BASELINE's LLaMA3-8B configuration at full size (32 layers, vocabulary 128256, 4096-token prompt: the long-KV
+    verify), device-drawn weights, graph replay: speculative == plain decoding for 10 tokens with forged acceptance and
+    every committed row's logits bit for bit; sampled LM-head logits against fp64 dot products."""
+    torch, P = env
+    sh = wl.LLAMA3_8B
+    named, head_rows = {}, {}
+    for name, tsr in wl.iter_device_weights(sh, "cuda"):
+        if name == "lm_head":
+            head_rows = {v: tsr[v].float().cpu().numpy() for v in (0, 31, 70000, 128255)}
+        named[name] = P.spec_pack_weight(tsr.contiguous()) if P.binding.is_packed_name(name) else tsr.contiguous()
+        del tsr
+    prompt = wl.make_prompt(sh)
+    gen = 10
+    cap = len(prompt) + 2 * gen + sh.tree_total + 40
+    plain = P.Engine(sh, named, tree=(1, 1, 1), max_seq=cap)
+    prec = []
+    greedy, _ = plain.generate(prompt, gen + 6, record=prec)
+    plain.close()
+    rng = np.random.default_rng(3)
+    spec = P.Engine(sh, named, max_seq=cap)
+    rec = []
+    got, taus = spec.generate(prompt, gen, tree_hook=forge_hook(greedy, len(prompt), lambda n: n % 4, rng, sh.vocab), record=rec)
+    spec.close()
+    assert got == greedy[:gen] and max(taus) >= 3
+    checked, deeper = assert_committed_rows_equal_plain(rec, prec)
+    assert checked >= len(rec) and deeper >= 2
+    r = rec[-1]
+    for v, w_row in head_rows.items():
+        want = r["feats"].astype(np.float64) @ w_row.astype(np.float64)
+        assert np.abs(r["logits"][:, v] - want).max() < 3e-3
+
+
+def test_full_depth_13b_bench_configuration_sampling(env):
+    """BASELINE's LLaMA2-13B configuration at full size (40 layers, T = 1, per-run seed), device-drawn weights, graph
+    replay: for five cycles the GPU's rejection-sampling decisions and bonus draws equal the oracle's rule applied to the
+    GPU's own logits; at T = 0 the same model's speculative output equals plain decoding."""
+    torch, P = env
+    sh = wl.LLAMA2_13B
+    named = P.pack_weights(wl.iter_device_weights(sh, "cuda"))
+    prompt = wl.make_prompt(sh)
+    seed = 77
+    eng = P.Engine(sh, named, seed=seed, max_seq=len(prompt) + 200)
+    eng.prefill(prompt)
+    for cycle in range(1, 6):
+        t = eng.draft_tree()
+        eng.verify(t)
+        lg = eng.logits(t.n_nodes)
+        ot = oracle.Tree(t.token[:t.n_nodes].copy(), t.parent[:t.n_nodes].copy(), t.depth[:t.n_nodes].copy(), t.score[:t.n_nodes].copy())
+        acc, bonus = oracle.accept_sample(ot, lg, sh.temperature, seed, cycle)
+        assert eng.accept(t) == [int(ot.token[j]) for j in acc] + [bonus]
+    eng.close()
+    gen = 8
+    plain = P.Engine(sh, named, tree=(1, 1, 1), temperature=0.0, max_seq=len(prompt) + 200)
+    greedy, _ = plain.generate(prompt, gen + 6)
+    plain.close()
+    rng = np.random.default_rng(4)
+    spec = P.Engine(sh, named, temperature=0.0, max_seq=len(prompt) + 200)
+    got, taus = spec.generate(prompt, gen, tree_hook=forge_hook(greedy, len(prompt), lambda n: n % 4, rng, sh.vocab))
+    spec.close()
+    assert got == greedy[:gen] and max(taus) >= 3
