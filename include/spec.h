@@ -66,7 +66,8 @@ typedef struct spec_config {
 
 /* DEVICE pointers, BORROWED for the life of the context, never written.
  * Projection matrices ([out, in], shapes in the comments) are in the library's
- * PACKED layout, produced once at load time by spec_pack_weight(); the
+ * PACKED layout, produced once at load time by spec_pack_weight() (the gate and
+ * up projections of the SwiGLU block together, by spec_pack_gate_up()); the
  * embedding table stays row-major (it is gathered by row); norm weights are
  * [d_model] vectors.  All in the configured dtype. */
 typedef struct spec_layer_weights {
@@ -74,7 +75,7 @@ typedef struct spec_layer_weights {
   const void *wq, *wk, *wv;   /* [n_q_heads*head_dim, d], [n_kv_heads*head_dim, d] x2 */
   const void *wo;             /* [d, n_q_heads*head_dim]                              */
   const void *ffn_norm;
-  const void *w_gate, *w_up;  /* [d_ffn, d]                                           */
+  const void *w_gate_up;      /* gate and up, [d_ffn, d] each, as ONE packed matrix (spec_pack_gate_up) */
   const void *w_down;         /* [d, d_ffn]                                           */
 } spec_layer_weights;
 
@@ -110,6 +111,17 @@ typedef struct spec_tree {
  *                       `stream`; src and dst must not overlap. */
 uint64_t spec_packed_bytes(int32_t dtype, int32_t rows, int32_t in);
 int spec_pack_weight(int32_t dtype, const void *src, int32_t rows, int32_t in, void *dst, void *stream);
+
+/* The gate and up projections of a SwiGLU feed-forward block (the target LLMs of
+ * Sec. 4.1 are LLaMA models: act = silu(x . w_gate) * (x . w_up)) as one packed
+ * matrix of 32 * ceil(rows / 16) rows: 32-row block b holds the gate rows
+ * 16 b .. 16 b + 15 followed by the up rows 16 b .. 16 b + 15 (zero rows past the
+ * last one), so that the wavefront that streams a block owns both sums of a
+ * column and applies the activation itself.  gate, up: DEVICE, row-major
+ * [rows, in]; dst: DEVICE, 256-byte aligned, spec_packed_gate_up_bytes large; no
+ * overlap; enqueued on `stream`.  Same argument checks and errors as above. */
+uint64_t spec_packed_gate_up_bytes(int32_t dtype, int32_t rows, int32_t in);
+int spec_pack_gate_up(int32_t dtype, const void *gate, const void *up, int32_t rows, int32_t in, void *dst, void *stream);
 
 /* Bytes of device workspace a context with this configuration needs (0 if the
  * configuration is invalid).  Host-only computation. */

@@ -22,7 +22,7 @@ lib = C.CDLL(_LIB_PATH)
 
 SPEC_OK, SPEC_EINVAL, SPEC_ESTATE, SPEC_ECAP, SPEC_EHIP = 0, -1, -2, -3, -4
 SPEC_MAX_DEPTH, SPEC_MAX_TOPK, SPEC_MAX_NODES = 15, 16, 128
-LAYER_FIELDS = ("attn_norm", "wq", "wk", "wv", "wo", "ffn_norm", "w_gate", "w_up", "w_down")
+LAYER_FIELDS = ("attn_norm", "wq", "wk", "wv", "wo", "ffn_norm", "w_gate_up", "w_down")
 
 
 class SpecError(RuntimeError):
@@ -82,10 +82,12 @@ lib.spec_last_error.argtypes = [C.c_void_p]
 lib.spec_packed_bytes.restype = C.c_uint64
 lib.spec_packed_bytes.argtypes = [C.c_int32, C.c_int32, C.c_int32]
 lib.spec_pack_weight.argtypes = [C.c_int32, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
+lib.spec_packed_gate_up_bytes.restype = C.c_uint64
+lib.spec_packed_gate_up_bytes.argtypes = [C.c_int32, C.c_int32, C.c_int32]
+lib.spec_pack_gate_up.argtypes = [C.c_int32, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
 lib.spec_k_gemm.argtypes = [C.c_int32, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_int32, C.c_void_p,
                             C.c_int32, C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p]
-lib.spec_k_gemm_swiglu.argtypes = [C.c_int32, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p,
-                                   C.c_void_p]
+lib.spec_k_gemm_swiglu.argtypes = [C.c_int32, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p]
 lib.spec_k_attention.argtypes = [C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
                                  C.c_int32, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p]
 lib.spec_k_topk_logprob.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
@@ -239,7 +241,23 @@ def spec_pack_weight(w):
     return dst
 
 
-PACKED_TENSORS = ("wq", "wk", "wv", "wo", "w_gate", "w_up", "w_down", "lm_head", "fc")
+def spec_pack_gate_up(w_gate, w_up):
+    """Row-major torch matrices [rows, in] on the device -> the one packed gate/up matrix (uint8 tensor)."""
+    import torch
+    assert w_gate.is_contiguous() and w_up.is_contiguous() and w_gate.dim() == 2 and w_gate.shape == w_up.shape and w_gate.dtype == w_up.dtype
+    dtype = 1 if w_gate.dtype == torch.bfloat16 else 0
+    n = int(lib.spec_packed_gate_up_bytes(dtype, w_gate.shape[0], w_gate.shape[1]))
+    if n == 0:
+        raise SpecError(SPEC_EINVAL, f"cannot pack {tuple(w_gate.shape)} {w_gate.dtype} gate/up matrices")
+    dst = torch.empty(n, dtype=torch.uint8, device=w_gate.device)
+    rc = lib.spec_pack_gate_up(dtype, w_gate.data_ptr(), w_up.data_ptr(), w_gate.shape[0], w_gate.shape[1], dst.data_ptr(), _stream_ptr())
+    if rc:
+        raise SpecError(rc, "spec_pack_gate_up")
+    dst.logical_shape = tuple(w_gate.shape)
+    return dst
+
+
+PACKED_TENSORS = ("wq", "wk", "wv", "wo", "w_down", "lm_head", "fc")
 
 
 def is_packed_name(name: str) -> bool:
@@ -266,14 +284,13 @@ def spec_k_gemm(x, ws: Sequence, n_split: int, m: Optional[int] = None):
 
 def spec_k_gemm_swiglu(x, w_gate, w_up, packed=None):
     """x: torch [m, in]; w_gate, w_up: row-major torch [rows, in] (packed here, per call: test use) -> act [m, rows].
-    packed: optional (packed gate, packed up) from an earlier call, to keep packing out of a timed loop."""
+    packed: optional packed gate/up matrix from spec_pack_gate_up, to keep packing out of a timed loop."""
     import torch
     dtype = 1 if x.dtype == torch.bfloat16 else 0
-    pg, pu = packed if packed is not None else (spec_pack_weight(w_gate.contiguous()), spec_pack_weight(w_up.contiguous()))
-    rows = pg.logical_shape[0]
+    pgu = packed if packed is not None else spec_pack_gate_up(w_gate.contiguous(), w_up.contiguous())
+    rows = pgu.logical_shape[0]
     act = torch.full((x.shape[0], rows), float("nan"), dtype=x.dtype, device=x.device)
-    rc = lib.spec_k_gemm_swiglu(dtype, x.data_ptr(), x.stride(0), x.shape[0], x.shape[1], pg.data_ptr(), pu.data_ptr(), rows,
-                                act.data_ptr(), _stream_ptr())
+    rc = lib.spec_k_gemm_swiglu(dtype, x.data_ptr(), x.stride(0), x.shape[0], x.shape[1], pgu.data_ptr(), rows, act.data_ptr(), _stream_ptr())
     if rc:
         raise SpecError(rc, "spec_k_gemm_swiglu")
     return act
@@ -408,14 +425,27 @@ def spec_topk_loss(feat_target, feat_draft, lm_head_packed, k: int, scratch=None
     return topk, ce, tot
 
 
-def pack_weights(named_tensors) -> Dict[str, "object"]:
-    """(name, row-major device tensor) pairs -> dict with every projection matrix in the packed layout.
-    Matrices are packed one at a time and the row-major original is dropped, so the peak extra memory
-    is one matrix."""
+def pack_weights(named_tensors, tap=None) -> Dict[str, "object"]:
+    """(name, row-major device tensor) pairs -> dict with every projection matrix in the packed layout; a layer's
+    w_gate and w_up (which must follow each other) become its w_gate_up.  Matrices are packed one at a time and the
+    row-major original is dropped, so the peak extra memory is one matrix (two for gate/up).  tap(name, tensor), if
+    given, sees every row-major tensor before it is packed."""
     out = {}
+    gate = None
     for name, t in named_tensors:
-        out[name] = spec_pack_weight(t.contiguous()) if is_packed_name(name) else t.contiguous()
+        if tap is not None:
+            tap(name, t)
+        leaf = name.rsplit(".", 1)[-1]
+        if leaf == "w_gate":
+            gate = (name, t.contiguous())
+        elif leaf == "w_up":
+            assert gate is not None and gate[0][:-len("w_gate")] == name[:-len("w_up")], "w_up must follow its layer's w_gate"
+            out[name[:-len("w_up")] + "w_gate_up"] = spec_pack_gate_up(gate[1], t.contiguous())
+            gate = None
+        else:
+            out[name] = spec_pack_weight(t.contiguous()) if is_packed_name(name) else t.contiguous()
         del t
+    assert gate is None, "w_gate without w_up"
     return out
 
 

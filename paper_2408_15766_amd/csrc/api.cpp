@@ -140,6 +140,9 @@ size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
 
 // The split count depends on the matrix shape only (never on the number of rows), so a token
 // sees the same summation order in plain decoding and inside a tree.
+// rows of the packed gate/up matrix: per 16 columns, 16 gate rows and 16 up rows
+int gate_up_rows(int f) { return 32 * ((f + 15) / 16); }
+
 GemmPlan plan_gemm(int total_rows, int in, int dtype) {
   const int blocks = (total_rows + 31) / 32;
   const int groups = (blocks + gemm_rows_per_group() / 32 - 1) / (gemm_rows_per_group() / 32);
@@ -194,7 +197,7 @@ size_t layout(const spec_config &c, spec_ctx *x, char *base) {
   const int max_parts = (c.max_seq + D * k) / kAttnPart + 2;   // parts of the longest row + the tail slot
   size_t part_floats = 0;
   {
-    struct { int rows, in; } g[5] = {{dq + 2 * dkv, d}, {d, dq}, {2 * f, d}, {d, f}, {d, 2 * d}};
+    struct { int rows, in; } g[5] = {{dq + 2 * dkv, d}, {d, dq}, {gate_up_rows(f), d}, {d, f}, {d, 2 * d}};
     for (auto &e : g) {
       GemmPlan p = plan_gemm(e.rows, e.in, c.dtype);
       part_floats = std::max(part_floats, (size_t)p.n_split * m_max * e.rows);
@@ -309,7 +312,7 @@ int run_gemm(spec_ctx *c, const void *x, int ldx, int m, int in, const Seg *segs
   for (int s = 0; s < 3; s++) {
     a.seg_w[s] = s < nseg ? segs[s].w : segs[0].w;
     a.seg_rows[s] = s < nseg ? segs[s].rows : 0;
-    a.seg_blocks[s] = (a.seg_rows[s] + 31) / 32;
+    a.seg_blocks[s] = swiglu_act ? (a.seg_rows[s] + 15) / 16 : (a.seg_rows[s] + 31) / 32;   // SwiGLU: rows = columns of act, 16 per block
     a.seg_col0[s] = col;
     col += a.seg_rows[s];
     blocks += a.seg_blocks[s];
@@ -360,17 +363,19 @@ int layer_forward(spec_ctx *c, const spec_layer_weights &lw, char *kcache, char 
     HIPCHK(c, launch_reduce_add_norm(dt, c->part, p.n_split, c->m_max, d, m, d, 1, lw.ffn_norm, g.rms_eps, c->h, c->x, c->stream));
   }
   {
-    // gate and up projections.  Without a K split a workgroup owns matching gate and up blocks and applies
-    // SwiGLU itself (no partial sums, no extra pass); with a K split the row kernel does it.
-    const Seg segs[2] = {{lw.w_gate, f}, {lw.w_up, f}};
-    const GemmPlan p = plan_gemm(2 * f, d, dt);
+    // gate and up projections, one packed matrix.  Without a K split a wavefront owns both sums of a column and
+    // applies SwiGLU itself (no partial sums, no extra pass); with a K split the row kernel does it.
+    const int gu = gate_up_rows(f);
+    const GemmPlan p = plan_gemm(gu, d, dt);
     if (p.n_split == 1) {
-      int rc = run_gemm(c, c->x, d, m, d, segs, 2, c->part, 2 * f, c->m_max, p, c->act);
+      const Seg segs[1] = {{lw.w_gate_up, f}};
+      int rc = run_gemm(c, c->x, d, m, d, segs, 1, c->part, gu, c->m_max, p, c->act);
       if (rc) return rc;
     } else {
-      int rc = run_gemm(c, c->x, d, m, d, segs, 2, c->part, 2 * f, c->m_max, p);
+      const Seg segs[1] = {{lw.w_gate_up, gu}};
+      int rc = run_gemm(c, c->x, d, m, d, segs, 1, c->part, gu, c->m_max, p);
       if (rc) return rc;
-      HIPCHK(c, launch_reduce_swiglu(dt, c->part, p.n_split, c->m_max, 2 * f, m, f, c->act, c->stream));
+      HIPCHK(c, launch_reduce_swiglu(dt, c->part, p.n_split, c->m_max, gu, m, f, c->act, c->stream));
     }
   }
   {
@@ -514,6 +519,18 @@ int spec_pack_weight(int32_t dtype, const void *src, int32_t rows, int32_t in, v
   return launch_pack_weight(dtype, src, rows, in, dst, (hipStream_t)stream) == hipSuccess ? SPEC_OK : SPEC_EHIP;
 }
 
+uint64_t spec_packed_gate_up_bytes(int32_t dtype, int32_t rows, int32_t in) {
+  if ((dtype != 0 && dtype != 1) || rows < 1 || in < 1 || in % (dtype == 1 ? 8 : 4)) return 0;
+  return packed_gate_up_bytes(dtype, rows, in);
+}
+
+int spec_pack_gate_up(int32_t dtype, const void *gate, const void *up, int32_t rows, int32_t in, void *dst, void *stream) {
+  if (!gate || !up || !dst || spec_packed_gate_up_bytes(dtype, rows, in) == 0 || ((uintptr_t)dst & 15) || ((uintptr_t)gate & 15) ||
+      ((uintptr_t)up & 15))
+    return SPEC_EINVAL;
+  return launch_pack_gate_up(dtype, gate, up, rows, in, dst, (hipStream_t)stream) == hipSuccess ? SPEC_OK : SPEC_EHIP;
+}
+
 uint64_t spec_workspace_bytes(const spec_config *cfg) {
   if (!config_ok(cfg, nullptr)) return 0;
   return layout(*cfg, nullptr, nullptr);
@@ -526,7 +543,7 @@ int spec_create(const spec_config *cfg, const spec_weights *w, spec_ctx **out) {
   if (!config_ok(cfg, &why)) return fail(nullptr, SPEC_EINVAL, "bad configuration: %s", why.c_str());
   if (!w || !w->embed || !w->lm_head || !w->final_norm || !w->layers || !w->draft_fc) return fail(nullptr, SPEC_EINVAL, "NULL weight pointer");
   auto layer_ok = [](const spec_layer_weights &l) {
-    return l.attn_norm && l.wq && l.wk && l.wv && l.wo && l.ffn_norm && l.w_gate && l.w_up && l.w_down;
+    return l.attn_norm && l.wq && l.wk && l.wv && l.wo && l.ffn_norm && l.w_gate_up && l.w_down;
   };
   for (int l = 0; l < cfg->n_layers; l++)
     if (!layer_ok(w->layers[l])) return fail(nullptr, SPEC_EINVAL, "NULL weight pointer in layer %d", l);
@@ -1030,22 +1047,21 @@ int spec_k_gemm(int32_t dtype, const void *x, int32_t ldx, int32_t m, int32_t in
   return launch_gemm(dtype, a, (hipStream_t)stream) == hipSuccess ? SPEC_OK : SPEC_EHIP;
 }
 
-int spec_k_gemm_swiglu(int32_t dtype, const void *x, int32_t ldx, int32_t m, int32_t in, const void *w_gate, const void *w_up,
-                       int32_t rows, void *act, void *stream) {
-  if (!x || !w_gate || !w_up || !act || rows < 1 || (dtype != 0 && dtype != 1)) return SPEC_EINVAL;
+int spec_k_gemm_swiglu(int32_t dtype, const void *x, int32_t ldx, int32_t m, int32_t in, const void *w_gate_up, int32_t rows, void *act,
+                       void *stream) {
+  if (!x || !w_gate_up || !act || rows < 1 || (dtype != 0 && dtype != 1)) return SPEC_EINVAL;
   const int epl = dtype == 1 ? 8 : 4;
   if (in < 1 || in % epl || ldx % epl || m < 1 || m > 4096) return SPEC_EINVAL;
   GemmArgs a{};
   a.x = x; a.ldx = ldx; a.m = m; a.in = in;
-  const void *ws[3] = {w_gate, w_up, w_gate};
   for (int s = 0; s < 3; s++) {
-    a.seg_w[s] = ws[s];
-    a.seg_rows[s] = s < 2 ? rows : 0;
-    a.seg_blocks[s] = s < 2 ? (rows + 31) / 32 : 0;
-    a.seg_col0[s] = s * rows;
+    a.seg_w[s] = w_gate_up;
+    a.seg_rows[s] = s == 0 ? rows : 0;
+    a.seg_blocks[s] = s == 0 ? (rows + 15) / 16 : 0;
+    a.seg_col0[s] = 0;
   }
-  a.nseg = 2; a.total_blocks = 2 * a.seg_blocks[0];
-  a.part = nullptr; a.ldp = 2 * rows; a.m_pad = m; a.n_split = 1;
+  a.nseg = 1; a.total_blocks = a.seg_blocks[0];
+  a.part = nullptr; a.ldp = gate_up_rows(rows); a.m_pad = m; a.n_split = 1;
   a.act = act;
   return launch_gemm(dtype, a, (hipStream_t)stream) == hipSuccess ? SPEC_OK : SPEC_EHIP;
 }

@@ -57,6 +57,25 @@ __device__ __forceinline__ void store_through(float *p, float v) {
   __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
+__device__ __forceinline__ void store_through(uint32_t *p, uint32_t v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+// Store of one activation value per lane, adjacent lanes holding adjacent columns of the same row (lane parity = column
+// parity).  bf16: the even lane writes its own and its neighbour's value (nx, fetched by the caller with a lane shift) as
+// one written-through dword when the row length is even (`pairs`: then p is 4-byte aligned for even columns); `next`
+// says that the neighbour's column exists.
+__device__ __forceinline__ void store_act(float *p, float r, float, bool ok, bool, bool, int) {
+  if (ok) store_through(p, r);
+}
+__device__ __forceinline__ void store_act(bf16_t *p, float r, float nx, bool ok, bool pairs, bool next, int lane) {
+  if (!ok) return;
+  if (!pairs) p->v = f32_to_bf16_bits(r);
+  else if (!(lane & 1)) {
+    if (next) store_through((uint32_t *)p, pack_bf16x2(r, nx));
+    else p->v = f32_to_bf16_bits(r);
+  }
+}
+
 // Butterfly reductions over the 64 lanes of a wavefront; every lane gets the result.
 // The exchange pattern is fixed, so the result does not depend on the data.
 __device__ __forceinline__ float wave_sum(float x) {

@@ -87,6 +87,41 @@ __device__ __forceinline__ void static_for(F &&f) {
   }
 }
 
+// SwiGLU epilogue of a block of the gate/up matrix.  Lane c < 16 holds the gate sums of column col = block * 16 + c
+// and lane c + 16 the up sums of the same column and tokens.  Each finishes half of the values (the low lane the
+// accumulator entries v < 8, the high lane v >= 8) after one exchange with its partner of the entries the partner
+// finishes.  In phases (all exchanges, all activations, all neighbour shifts, all stores), so that the lane exchanges
+// overlap instead of each waiting for the one before.  act: the block's first token row, column col.
+template <typename T, int TB>
+__device__ __forceinline__ void swiglu_epilogue(const f32x16_t (&acc)[TB], T *act, int f, int col, bool store, int m_loc, int c, int g) {
+  const bool hi = c >= 16;
+  float r[TB][8], nx[TB][8];
+#pragma unroll
+  for (int t = 0; t < TB; t++)
+#pragma unroll
+    for (int v8 = 0; v8 < 8; v8++) r[t][v8] = __shfl_xor(hi ? acc[t][v8] : acc[t][8 + v8], 16, 64);
+#pragma unroll
+  for (int t = 0; t < TB; t++)
+#pragma unroll
+    for (int v8 = 0; v8 < 8; v8++) {
+      const float mine = hi ? acc[t][8 + v8] : acc[t][v8], other = r[t][v8];
+      r[t][v8] = silu_mul(hi ? other : mine, hi ? mine : other);
+    }
+#pragma unroll
+  for (int t = 0; t < TB; t++)
+#pragma unroll
+    for (int v8 = 0; v8 < 8; v8++) nx[t][v8] = __shfl_down(r[t][v8], 1, 64);
+  const bool pairs = (f & 1) == 0, next = col + 1 < f;
+#pragma unroll
+  for (int t = 0; t < TB; t++)
+#pragma unroll
+    for (int v8 = 0; v8 < 8; v8++) {
+      const int v = hi ? 8 + v8 : v8;
+      const int i = t * 32 + 8 * (v >> 2) + 4 * g + (v & 3);
+      store_act(act + (size_t)i * f, r[t][v8], nx[t][v8], store && i < m_loc, pairs, next, c);
+    }
+}
+
 template <typename T, int TB>
 __global__ __launch_bounds__(kGemmThreads, (TB <= 2 && kStages <= 3) ? 2 : 1) void gemm_stream_kernel(GemmArgs a) {
   constexpr int EPL = GemmTraits<T>::kEpl;
@@ -102,14 +137,13 @@ __global__ __launch_bounds__(kGemmThreads, (TB <= 2 && kStages <= 3) ? 2 : 1) vo
   // argument struct: that would push it to private memory).
   // A wave past the last block recomputes the last block and stores nothing, so that every wave
   // runs the same branch-free loop and the same barriers.
-  // SwiGLU mode pairs blocks instead: waves 0,1 take gate blocks 2x, 2x+1 and waves 2,3 the same up blocks.
+  // SwiGLU mode streams the one gate/up matrix (see pack_gate_up_kernel): a block holds 16 gate rows in the lanes
+  // c < 16 and the up rows of the same 16 columns in the lanes c >= 16; seg_rows[0] is the number of columns.
   const int bx = blockIdx.x, by = blockIdx.y, mt = 0;
   const int m_loc = a.m;                                       // (more than 128 rows go to gemm_tiled_kernel)
   const bool swiglu = a.act != nullptr;
   const int e0 = a.seg_blocks[0], e1 = e0 + (a.nseg > 1 ? a.seg_blocks[1] : 0);
-  const int half_waves = kGemmWaves / 2;
-  const int pair_raw = bx * half_waves + (wave % half_waves);
-  const int blk_raw = swiglu ? (pair_raw < e0 ? (wave / half_waves) * e0 + pair_raw : a.total_blocks) : bx * kGemmWaves + wave;
+  const int blk_raw = bx * kGemmWaves + wave;
   const bool active = blk_raw < a.total_blocks;
   const int blk = active ? blk_raw : a.total_blocks - 1;
   const int seg = blk < e0 ? 0 : (blk < e1 ? 1 : 2);
@@ -224,35 +258,8 @@ __global__ __launch_bounds__(kGemmThreads, (TB <= 2 && kStages <= 3) ? 2 : 1) vo
   for (; s < n_slab; s += kPeriod) period(std::false_type{}, s);
 
   if (swiglu) {
-    // Gate wave w and up wave w + half_waves hold the same (columns, tokens).  Each finishes half of the values: the
-    // gate wave the accumulator entries v < 8, the up wave v >= 8, after the two have swapped the halves the other needs
-    // through LDS (the X slabs are no longer needed; value-major, lane-minor layout: no bank conflicts).
-    float *xch = (float *)lds;                                // [wave][TB * 8 values][64 lanes]
-    const bool is_up = wave >= half_waves;
-    const int v_mine = is_up ? 8 : 0, v_theirs = is_up ? 0 : 8;
-    __syncthreads();
-    {
-      float *dst = xch + (size_t)wave * (TB * 8 * 64) + lane;
-#pragma unroll
-      for (int t = 0; t < TB; t++)
-#pragma unroll
-        for (int v = 0; v < 8; v++) dst[(t * 8 + v) * 64] = is_up ? acc[t][v] : acc[t][8 + v];   // what the partner finishes
-    }
-    __syncthreads();
-    if (!active || row >= seg_rows) return;
-    const float *src = xch + (size_t)(is_up ? wave - half_waves : wave + half_waves) * (TB * 8 * 64) + lane;
-    T *act = (T *)a.act + (size_t)mt * 128 * seg_rows + row;
-    (void)v_theirs;
-#pragma unroll
-    for (int t = 0; t < TB; t++)
-#pragma unroll
-      for (int v8 = 0; v8 < 8; v8++) {
-        const int v = v_mine + v8;
-        const int i = t * 32 + 8 * (v >> 2) + 4 * g + (v & 3);
-        const float mine = is_up ? acc[t][8 + v8] : acc[t][v8], other = src[(t * 8 + v8) * 64];
-        const float gv = is_up ? other : mine, uv = is_up ? mine : other;
-        if (i < m_loc) act[(size_t)i * seg_rows] = from_f32<T>(silu_mul(gv, uv));
-      }
+    const int col = blk * 16 + (c & 15);
+    swiglu_epilogue<T, TB>(acc, (T *)a.act + (size_t)mt * 128 * seg_rows + col, seg_rows, col, active && col < seg_rows, m_loc, c, g);
     return;
   }
   if (!active || row >= seg_rows) return;
@@ -270,8 +277,9 @@ __global__ __launch_bounds__(kGemmThreads, (TB <= 2 && kStages <= 3) ? 2 : 1) vo
 // The same contraction when X has several 128-row tiles.  One launch covers all tiles; a workgroup owns
 // (256 weight rows, one K split, one tile).  Here the matrix cores are the limit, and with one weight block
 // per wave every MFMA would need its own token fragment from LDS (LDS bandwidth runs out first), so a wave
-// streams TWO weight blocks and uses each fragment twice.  In SwiGLU mode the two blocks are the gate and
-// the up block of the same columns, so the activation is formed in registers.  Tiles of the same weight rows
+// streams TWO weight blocks and uses each fragment twice.  In SwiGLU mode the blocks are those of the gate/up
+// matrix (gate rows in the lanes c < 16, up rows of the same columns in the lanes c >= 16) and the activation is
+// formed in registers after one exchange between the two lane halves.  Tiles of the same weight rows
 // take workgroup ids 8 apart inside a window of 8 * m_tiles ids: they run together on one XCD and share the
 // weights through its L2 (default cache policy instead of the read-once hint).
 template <typename T>
@@ -295,8 +303,8 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_tiled_kernel(GemmArgs a)
 
   const bool swiglu = a.act != nullptr;
   const int e0 = a.seg_blocks[0], e1 = e0 + (a.nseg > 1 ? a.seg_blocks[1] : 0);
-  const int unit = bx * kGemmWaves + wave;                     // pair of blocks (SwiGLU: gate/up pair of the same columns)
-  bool active[WB]; int seg_rows[WB], seg_col0[WB], row[WB];
+  const int unit = bx * kGemmWaves + wave;                     // pair of consecutive blocks
+  bool active[WB]; int seg_rows[WB], seg_col0[WB], row[WB], blk_of[WB];
   const char *wstream[WB];
   constexpr int KSLAB = kSlabRowBytes / (int)sizeof(T);
   const int n_it_total = (a.in + KI - 1) / KI;
@@ -308,9 +316,10 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_tiled_kernel(GemmArgs a)
   const int n_slab = (n_iter + kSlabIters - 1) / kSlabIters;
 #pragma unroll
   for (int wb = 0; wb < WB; wb++) {
-    const int blk_raw = swiglu ? (unit < e0 ? wb * e0 + unit : a.total_blocks) : unit * WB + wb;
+    const int blk_raw = unit * WB + wb;
     active[wb] = blk_raw < a.total_blocks;
     const int blk = active[wb] ? blk_raw : a.total_blocks - 1;
+    blk_of[wb] = blk;
     const int seg = blk < e0 ? 0 : (blk < e1 ? 1 : 2);
     const int b0 = seg == 0 ? 0 : (seg == 1 ? e0 : e1);
     seg_rows[wb] = seg == 0 ? a.seg_rows[0] : (seg == 1 ? a.seg_rows[1] : a.seg_rows[2]);
@@ -403,16 +412,12 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_tiled_kernel(GemmArgs a)
   }
 
   if (swiglu) {
-    if (!active[0] || row[0] >= seg_rows[0]) return;
-    T *act = (T *)a.act + (size_t)mt * 128 * seg_rows[0] + row[0];
+    const int f = a.seg_rows[0];
 #pragma unroll
-    for (int t = 0; t < TB; t++)
-#pragma unroll
-      for (int v = 0; v < 16; v++) {
-        const int i = t * 32 + 8 * (v >> 2) + 4 * g + (v & 3);
-        const float gv = acc[0][t][v], uv = acc[1][t][v];
-        if (i < m_loc) act[(size_t)i * seg_rows[0]] = from_f32<T>(silu_mul(gv, uv));
-      }
+    for (int wb = 0; wb < WB; wb++) {
+      const int col = blk_of[wb] * 16 + (c & 15);
+      swiglu_epilogue<T, TB>(acc[wb], (T *)a.act + (size_t)mt * 128 * f + col, f, col, active[wb] && col < f, m_loc, c, g);
+    }
     return;
   }
 #pragma unroll
@@ -447,6 +452,48 @@ __global__ __launch_bounds__(256) void pack_weight_kernel(const T *src, int rows
     if (row < rows && k < in) v = *(const u32x4_t *)(src + (size_t)row * in + k);     // in % EPL == 0: whole piece in range
     dst[p] = v;
   }
+}
+
+// The gate and up projections as ONE packed matrix: block b holds, in the row order of the layout above, the gate
+// rows 16 b .. 16 b + 15 and then the up rows 16 b .. 16 b + 15 (zero rows past the last column), so that one wave
+// owns both sums of a column and SwiGLU needs no second pass and no exchange between waves.
+template <typename T>
+__global__ __launch_bounds__(256) void pack_gate_up_kernel(const T *gate, const T *up, int rows, int in, u32x4_t *dst, size_t n_pieces) {
+  constexpr int EPL = GemmTraits<T>::kEpl;
+  constexpr int KI = 2 * kLaneBytes / (int)sizeof(T);
+  const int n_it = (in + KI - 1) / KI;
+  for (size_t p = (size_t)blockIdx.x * 256 + threadIdx.x; p < n_pieces; p += (size_t)gridDim.x * 256) {
+    const int lane = (int)(p & 63), j = (int)((p >> 6) & 7);
+    const size_t tile = p >> 9;
+    const int it = (int)(tile % n_it);
+    const int rb = (int)(tile / n_it);
+    const int c = lane & 31;
+    const int row = rb * 16 + (c & 15);
+    const T *src = c < 16 ? gate : up;
+    const int k = it * KI + (lane >> 5) * (KI / 2) + j * EPL;
+    u32x4_t v = {0u, 0u, 0u, 0u};
+    if (row < rows && k < in) v = *(const u32x4_t *)(src + (size_t)row * in + k);
+    dst[p] = v;
+  }
+}
+
+size_t packed_gate_up_bytes(int dtype, int rows, int in) {
+  const int ki = gemm_k_per_iter(dtype);
+  return (size_t)((rows + 15) / 16) * (size_t)((in + ki - 1) / ki) * kTileBytes;
+}
+
+hipError_t launch_pack_gate_up(int dtype, const void *gate, const void *up, int rows, int in, void *dst, hipStream_t st) {
+  const int epl = dtype == 1 ? 8 : 4;
+  if (rows < 1 || in < 1 || in % epl) return hipErrorInvalidValue;
+  const size_t n_pieces = packed_gate_up_bytes(dtype, rows, in) / 16;
+  const int blocks = (int)std::min<size_t>((n_pieces + 255) / 256, 65536);
+  if (dtype == 1)
+    hipLaunchKernelGGL(pack_gate_up_kernel<bf16_t>, dim3(blocks), dim3(256), 0, st, (const bf16_t *)gate, (const bf16_t *)up, rows, in,
+                       (u32x4_t *)dst, n_pieces);
+  else
+    hipLaunchKernelGGL(pack_gate_up_kernel<float>, dim3(blocks), dim3(256), 0, st, (const float *)gate, (const float *)up, rows, in,
+                       (u32x4_t *)dst, n_pieces);
+  return hipGetLastError();
 }
 
 size_t packed_weight_bytes(int dtype, int rows, int in) {
@@ -499,13 +546,11 @@ static hipError_t launch_t(GemmArgs a, hipStream_t st) {
   a.m_tiles = (a.m + 127) / 128;
   const int tb = a.m_tiles > 1 ? 4 : (a.m + 31) / 32;
   a.grid_x = (a.total_blocks + kGemmWaves - 1) / kGemmWaves;
-  if (a.act != nullptr) {                                      // SwiGLU mode: one workgroup per two gate/up block pairs
-    if (a.nseg != 2 || a.n_split != 1 || a.seg_rows[0] != a.seg_rows[1] || (kGemmWaves & 1)) return hipErrorInvalidValue;
-    a.grid_x = (a.seg_blocks[0] + kGemmWaves / 2 - 1) / (kGemmWaves / 2);
-  }
+  // SwiGLU mode: the one gate/up matrix, 16 columns per block, whole K (the activation is not linear)
+  if (a.act != nullptr && (a.nseg != 1 || a.n_split != 1 || a.seg_blocks[0] != (a.seg_rows[0] + 15) / 16)) return hipErrorInvalidValue;
   dim3 grid(a.grid_x, a.n_split);
   if (a.m_tiles > 1) {                                         // two blocks per wave; see gemm_tiled_kernel's id decoding
-    a.grid_x = a.act != nullptr ? (a.seg_blocks[0] + kGemmWaves - 1) / kGemmWaves : (a.total_blocks + 2 * kGemmWaves - 1) / (2 * kGemmWaves);
+    a.grid_x = (a.total_blocks + 2 * kGemmWaves - 1) / (2 * kGemmWaves);
     const dim3 tgrid((a.grid_x * a.n_split + 7) / 8 * 8 * a.m_tiles, 1);
     hipLaunchKernelGGL((gemm_tiled_kernel<T>), tgrid, dim3(kGemmThreads), (size_t)2 * 4 * 32 * kSlabStride, st, a);
     return hipGetLastError();

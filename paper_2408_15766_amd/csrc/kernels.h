@@ -58,6 +58,9 @@ int gemm_rows_per_group();
 // Packed layout of a row-major [rows, in] matrix (see gemm.hip): size in bytes, and the out-of-place repack.
 size_t packed_weight_bytes(int dtype, int rows, int in);
 hipError_t launch_pack_weight(int dtype, const void *src, int rows, int in, void *dst, hipStream_t st);
+// gate and up ([rows, in] each, row-major) as one packed matrix: 16 gate rows, then the 16 up rows of the same columns, per block
+size_t packed_gate_up_bytes(int dtype, int rows, int in);
+hipError_t launch_pack_gate_up(int dtype, const void *gate, const void *up, int rows, int in, void *dst, hipStream_t st);
 
 // ---- rowops.hip ------------------------------------------------------------------------------
 // h[i] = embed[token[i]] (fp32);  x[i] = rmsnorm(h[i]) * w  in the storage type.

@@ -287,10 +287,12 @@ __global__ __launch_bounds__(kRowThreads) void reduce_swiglu_kernel(const float 
   const int i = blockIdx.y;
   const int c = blockIdx.x * kRowThreads + threadIdx.x;
   if (c >= f) return;
-  float g = part[(size_t)i * ldp + c], u = part[(size_t)i * ldp + f + c];
+  // the partial sums follow the rows of the packed gate/up matrix: per 16 columns, 16 gate sums and then 16 up sums
+  const int cg = (c >> 4) * 32 + (c & 15), cu = cg + 16;
+  float g = part[(size_t)i * ldp + cg], u = part[(size_t)i * ldp + cu];
   for (int s = 1; s < n_split; s++) {
-    g += part[((size_t)s * m_pad + i) * ldp + c];
-    u += part[((size_t)s * m_pad + i) * ldp + f + c];
+    g += part[((size_t)s * m_pad + i) * ldp + cg];
+    u += part[((size_t)s * m_pad + i) * ldp + cu];
   }
   act[(size_t)i * f + c] = from_f32<T>(silu_mul(g, u));
 }

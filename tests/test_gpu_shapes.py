@@ -155,13 +155,12 @@ def test_full_depth_70b_bench_configuration(env):
     feature rows with the head's rows."""
     torch, P = env
     sh = wl.LLAMA3_70B
-    named = {}
     head_rows = {}
-    for name, tsr in wl.iter_device_weights(sh, "cuda"):
+
+    def tap(name, tsr):
         if name == "lm_head":
-            head_rows = {v: tsr[v].float().cpu().numpy() for v in (0, 1, 4097, 128255)}
-        named[name] = P.spec_pack_weight(tsr.contiguous()) if P.binding.is_packed_name(name) else tsr.contiguous()
-        del tsr
+            head_rows.update({v: tsr[v].float().cpu().numpy() for v in (0, 1, 4097, 128255)})
+    named = P.pack_weights(wl.iter_device_weights(sh, "cuda"), tap=tap)
     prompt = wl.make_prompt(sh)
     gen = 10
     cap = len(prompt) + 2 * gen + sh.tree_total + 40
@@ -189,12 +188,12 @@ def test_full_depth_8b_bench_configuration(env):
     every committed row's logits bit for bit; sampled LM-head logits against fp64 dot products."""
     torch, P = env
     sh = wl.LLAMA3_8B
-    named, head_rows = {}, {}
-    for name, tsr in wl.iter_device_weights(sh, "cuda"):
+    head_rows = {}
+
+    def tap(name, tsr):
         if name == "lm_head":
-            head_rows = {v: tsr[v].float().cpu().numpy() for v in (0, 31, 70000, 128255)}
-        named[name] = P.spec_pack_weight(tsr.contiguous()) if P.binding.is_packed_name(name) else tsr.contiguous()
-        del tsr
+            head_rows.update({v: tsr[v].float().cpu().numpy() for v in (0, 31, 70000, 128255)})
+    named = P.pack_weights(wl.iter_device_weights(sh, "cuda"), tap=tap)
     prompt = wl.make_prompt(sh)
     gen = 10
     cap = len(prompt) + 2 * gen + sh.tree_total + 40
