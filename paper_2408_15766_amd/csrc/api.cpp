@@ -148,12 +148,16 @@ GemmPlan plan_gemm(int total_rows, int in, int dtype) {
   const int groups = (blocks + gemm_rows_per_group() / 32 - 1) / (gemm_rows_per_group() / 32);
   const int kslab = gemm_k_per_slab(dtype);
   const int slabs = (in + kslab - 1) / kslab;
-  // Measured on MI355X: streaming is fastest with the fewest K splits that still put a workgroup on
-  // most of the 256 CUs (each extra split adds a partial-sum round trip and shortens the streams);
-  // power-of-two counts keep the K ranges even.
-  int s = 1;
-  while (groups * s < 160 && s < 8) s *= 2;
-  while (s > 1 && slabs / s < 4) s /= 2;                          // keep >= 4 slabs per split
+  // Measured on MI355X: a launch streams fastest when its workgroups (groups x splits) cover the 256 compute units once
+  // (more than 256 is slower again: 13B down projection, 27 us with 240 workgroups, 33 us with 320) and the longest
+  // K range, ceil(slabs / splits), is as short as possible; among equals the fewest splits (each adds a partial-sum
+  // round trip), and at least 4 slabs per split.  Counts that are not powers of two are fine: 40 groups x 6 splits.
+  int s = 1, longest = slabs;
+  for (int cand = 2; cand <= 8 && groups * cand <= 256 && slabs / cand >= 4; cand++) {
+    const int len = (slabs + cand - 1) / cand;
+    if (len < longest) { longest = len; s = cand; }
+  }
+  if (s == 1 && groups < 160 && slabs / 2 >= 4) s = 2;           // 129 .. 159 groups: two workgroups per compute unit beat half a chip
   GemmPlan p;
   p.n_split = s;
   return p;

