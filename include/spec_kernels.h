@@ -36,7 +36,7 @@ int spec_k_gemm(int32_t dtype, const void *x, int32_t ldx, int32_t m, int32_t in
  * launch's epilogue: act[i][c] = silu(x[i] . w_gate[c]) * (x[i] . w_up[c]), silu(g)
  * = g / (1 + exp(-g)), fp32 accumulation, rounded once to `dtype`.  w_gate_up: the
  * two [rows, in] matrices packed together by spec_pack_gate_up(); x: [m, in] with
- * row stride ldx; act: [m, rows] in `dtype`; 1 <= m <= 4096.  K is not split (the
+ * row stride ldx; act: [m, rows] contiguous in `dtype`, 4-byte aligned; 1 <= m <= 4096.  K is not split (the
  * decode path uses this form whenever the projection has enough 32-row blocks to
  * fill the chip without a split). */
 int spec_k_gemm_swiglu(int32_t dtype, const void *x, int32_t ldx, int32_t m, int32_t in, const void *w_gate_up, int32_t rows, void *act,

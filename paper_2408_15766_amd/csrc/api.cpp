@@ -1053,7 +1053,7 @@ int spec_k_gemm(int32_t dtype, const void *x, int32_t ldx, int32_t m, int32_t in
 
 int spec_k_gemm_swiglu(int32_t dtype, const void *x, int32_t ldx, int32_t m, int32_t in, const void *w_gate_up, int32_t rows, void *act,
                        void *stream) {
-  if (!x || !w_gate_up || !act || rows < 1 || (dtype != 0 && dtype != 1)) return SPEC_EINVAL;
+  if (!x || !w_gate_up || !act || ((uintptr_t)act & 3) || rows < 1 || (dtype != 0 && dtype != 1)) return SPEC_EINVAL;
   const int epl = dtype == 1 ? 8 : 4;
   if (in < 1 || in % epl || ldx % epl || m < 1 || m > 4096) return SPEC_EINVAL;
   GemmArgs a{};

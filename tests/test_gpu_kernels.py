@@ -68,10 +68,12 @@ def test_gemm_matches_matmul(env, dtype, m, k, rows, n_split):
     assert np.abs(got - want).max() < tol
 
 
-@pytest.mark.parametrize("dtype,m,k,rows", [("fp32", 16, 256, 688), ("bf16", 60, 4096, 1100), ("bf16", 1, 1280, 64), ("bf16", 200, 768, 300)])
+@pytest.mark.parametrize("dtype,m,k,rows", [("fp32", 16, 256, 688), ("bf16", 60, 4096, 1100), ("bf16", 1, 1280, 64), ("bf16", 200, 768, 300),
+                                            ("bf16", 40, 256, 77), ("fp32", 33, 128, 77), ("bf16", 60, 512, 15), ("bf16", 130, 256, 45)])
 def test_gemm_swiglu_epilogue_matches_oracle(env, dtype, m, k, rows):
-    """Gate and up projections with SwiGLU applied inside the launch: silu(x.wg) * (x.wu) against fp64, ragged 32-row
-    blocks, one row, and two 128-row tiles (the prefill form).  bf16 storage rounds the result once (relative 2^-9)."""
+    """Gate and up projections with SwiGLU applied inside the launch: silu(x.wg) * (x.wu) against fp64, ragged 16-column
+    blocks, one row, two 128-row tiles (the prefill form), an odd number of columns (no paired stores) and fewer columns
+    than one block.  bf16 storage rounds the result once (relative 2^-9)."""
     torch, P = env
     rng = np.random.default_rng(case_seed("swiglu", dtype, m, k, rows))
     x = rand_storage(rng, (m, k), dtype)
