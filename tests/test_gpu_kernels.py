@@ -89,6 +89,55 @@ def test_gemm_swiglu_epilogue_matches_oracle(env, dtype, m, k, rows):
     assert (np.abs(got - want) <= tol).all()
 
 
+def expected_packed(rows_of_block, n_blocks, k_elems, esz, src_bytes_of_row):
+    """The packed layout written out from its definition: tiles of 32 rows x 256 bytes of k, tiles of a block consecutive
+    along k, piece (j, lane) of a tile at byte j*1024 + lane*16 = row lane%32, k-bytes (lane/32)*128 + j*16 .. +16 of the
+    tile; zero beyond the matrix.  rows_of_block(b, c) -> source row or None; src_bytes_of_row(r) -> the row as bytes."""
+    row_bytes = k_elems * esz
+    n_it = (row_bytes + 255) // 256
+    out = np.zeros((n_blocks, n_it, 8, 64, 16), dtype=np.uint8)
+    for b in range(n_blocks):
+        for c in range(32):
+            r = rows_of_block(b, c)
+            if r is None:
+                continue
+            src = np.zeros(n_it * 256, dtype=np.uint8)
+            src[:row_bytes] = src_bytes_of_row(r)
+            t = src.reshape(n_it, 2, 8, 16)                      # [tile][half g][piece j][16 bytes]
+            for g in range(2):
+                out[b, :, :, g * 32 + c, :] = t[:, g]
+    return out.reshape(-1)
+
+
+@pytest.mark.parametrize("dtype,rows,k", [("bf16", 77, 200), ("fp32", 45, 100), ("bf16", 64, 256)])
+def test_packed_layouts_match_their_definition(env, dtype, rows, k):
+    """spec_pack_weight and spec_pack_gate_up against the layout the header defines, byte for byte: ragged rows, ragged
+    k, zero padding; gate/up: block b = gate rows 16b..16b+15 then up rows 16b..16b+15."""
+    torch, P = env
+    rng = np.random.default_rng(case_seed("pack", dtype, rows, k))
+    esz = 2 if dtype == "bf16" else 4
+    w, u = rand_storage(rng, (rows, k), dtype), rand_storage(rng, (rows, k), dtype)
+    dw, du = to_dev(torch, w, dtype), to_dev(torch, u, dtype)
+    raw = lambda t: t.contiguous().view(torch.uint8).cpu().numpy().reshape(rows, k * esz)
+    bw, bu = raw(dw), raw(du)
+    got = P.spec_pack_weight(dw)
+    nb = (rows + 31) // 32
+    want = expected_packed(lambda b, c: b * 32 + c if b * 32 + c < rows else None, nb, k, esz, lambda r: bw[r])
+    assert got.numel() == want.size == P.spec_packed_bytes(1 if dtype == "bf16" else 0, rows, k)
+    assert np.array_equal(got.cpu().numpy(), want)
+    got = P.spec_pack_gate_up(dw, du)
+    nb = (rows + 15) // 16
+
+    def src_row(b, c):
+        r = b * 16 + (c & 15)
+        return (r if c < 16 else rows + r) if r < rows else None
+    both = np.concatenate([bw, bu])
+    want = expected_packed(src_row, nb, k, esz, lambda r: both[r])
+    assert got.numel() == want.size
+    assert np.array_equal(got.cpu().numpy(), want)
+    assert P.spec_packed_bytes(1, 32, 12) == 0 and P.binding.lib.spec_packed_gate_up_bytes(0, 32, 6) == 0      # k not a whole 16-byte piece
+
+
 def test_gemm_row_is_independent_of_batch(env):
     """A row computed alone (plain decoding) is bit-identical to the same row inside a 60-row tree."""
     torch, P = env
