@@ -145,19 +145,26 @@ int gate_up_rows(int f) { return 32 * ((f + 15) / 16); }
 
 GemmPlan plan_gemm(int total_rows, int in, int dtype) {
   const int blocks = (total_rows + 31) / 32;
-  const int groups = (blocks + gemm_rows_per_group() / 32 - 1) / (gemm_rows_per_group() / 32);
   const int kslab = gemm_k_per_slab(dtype);
   const int slabs = (in + kslab - 1) / kslab;
-  // Measured on MI355X: a launch streams fastest when its workgroups (groups x splits) cover the 256 compute units once
-  // (more than 256 is slower again: 13B down projection, 27 us with 240 workgroups, 33 us with 320) and the longest
-  // K range, ceil(slabs / splits), is as short as possible; among equals the fewest splits (each adds a partial-sum
-  // round trip), and at least 4 slabs per split.  Counts that are not powers of two are fine: 40 groups x 6 splits.
-  int s = 1, longest = slabs;
-  for (int cand = 2; cand <= 8 && groups * cand <= 256 && slabs / cand >= 4; cand++) {
-    const int len = (slabs + cand - 1) / cand;
-    if (len < longest) { longest = len; s = cand; }
-  }
-  if (s == 1 && groups < 160 && slabs / 2 >= 4) s = 2;           // 129 .. 159 groups: two workgroups per compute unit beat half a chip
+  // Every wave streams one (32-row block, K range) unit and the launch spreads its units over all compute units
+  // whatever the split count, so the count only trades parallel streams against partial-sum traffic.  Measured on
+  // MI355X over the projections of the four benchmark shapes (M = 60):
+  //  * at least 4 slabs per split, at most 8 splits;
+  //  * the smallest count with 512 units or more (two streaming waves per compute unit): below that the launch is
+  //    slower (7B O projection, 256 units 13.3 us, 512 units 9.8 us), above it each further split costs more in partial
+  //    sums than it gains (7B down 20.6 us with 4 splits, 21.0 with 8; 70B O 26.0 with 2, 28.8 with 4);
+  //  * a count up to twice that which divides the slabs evenly is taken instead (13B down, 54 slabs: 28.5 us with 4
+  //    splits, 27.7 with 6; 8B QKV, 16 slabs: 12.5 us with 4);
+  //  * streams that stay longer than 24 slabs are halved again while the units fit the chip's 1024 SIMDs (70B down,
+  //    112 slabs: 80.8 us with 2 splits, 76.4 with 4).
+  int smax = 1;
+  while (smax < 8 && slabs / (smax + 1) >= 4) smax++;
+  int s = 1;
+  while (s < smax && blocks * s < 512) s++;
+  for (int c = s; c <= smax && c <= 2 * s; c++)
+    if (slabs % c == 0) { s = c; break; }
+  while (2 * s <= smax && slabs / (2 * s) >= 24 && blocks * 2 * s <= 1024) s *= 2;
   GemmPlan p;
   p.n_split = s;
   return p;

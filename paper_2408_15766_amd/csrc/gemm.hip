@@ -143,7 +143,7 @@ __global__ __launch_bounds__(kGemmThreads, (TB <= 2 && kStages <= 3) ? 2 : 1) vo
   const int m_loc = a.m;                                       // (more than 128 rows go to gemm_tiled_kernel)
   const bool swiglu = a.act != nullptr;
   const int e0 = a.seg_blocks[0], e1 = e0 + (a.nseg > 1 ? a.seg_blocks[1] : 0);
-  const int blk_raw = bx * kGemmWaves + wave;
+  const int blk_raw = bx * a.blk_per_wg + wave * a.blk_per_wave;   // four adjacent blocks, or strided over more workgroups: see launch_t
   const bool active = blk_raw < a.total_blocks;
   const int blk = active ? blk_raw : a.total_blocks - 1;
   const int seg = blk < e0 ? 0 : (blk < e1 ? 1 : 2);
@@ -162,6 +162,8 @@ __global__ __launch_bounds__(kGemmThreads, (TB <= 2 && kStages <= 3) ? 2 : 1) vo
   const int k_begin = it_begin * KI;
   const int n_iter = it_end - it_begin;
   const int n_slab = (n_iter + kSlabIters - 1) / kSlabIters;
+  // A wave without a block of its own only helps to stage the X slabs (same barriers, no weight loads, no MFMAs).
+  const int n_iter_w = __builtin_amdgcn_readfirstlane(active ? n_iter : 0);
   // this wave's stream: tiles it_begin .. it_end of row block (blk - b0), one contiguous region
   const char *wstream = (const char *)seg_w + ((size_t)(blk - b0) * n_it_total + it_begin) * (size_t)kTileBytes + lane * 16;
 
@@ -217,7 +219,7 @@ __global__ __launch_bounds__(kGemmThreads, (TB <= 2 && kStages <= 3) ? 2 : 1) vo
   load_x(0);
 #pragma unroll
   for (int it = 0; it < kStages - 1; it++)
-    if (it < n_iter) load_w(ring[it], it);
+    if (it < n_iter_w) load_w(ring[it], it);
   store_x(0);
   __syncthreads();
 
@@ -239,9 +241,9 @@ __global__ __launch_bounds__(kGemmThreads, (TB <= 2 && kStages <= 3) ? 2 : 1) vo
       const int it = S * kSlabIters + ii;
       // stage indices are compile-time after unrolling
       const int st_use = (base_stage + ii) % kStages, st_load = (base_stage + ii + kStages - 1) % kStages;
-      if (FAST || it + kStages - 1 < n_iter) load_w(ring[st_load], it + kStages - 1);
+      if (FAST || it + kStages - 1 < n_iter_w) load_w(ring[st_load], it + kStages - 1);
       __builtin_amdgcn_sched_barrier(0);                     // keep the prefetch ahead of the MFMAs
-      if (FAST || it < n_iter) compute(ring[st_use], buf, ii);
+      if (FAST || it < n_iter_w) compute(ring[st_use], buf, ii);
       __builtin_amdgcn_sched_barrier(0);
     }
     if (more) store_x(buf ^ 1);
@@ -252,7 +254,7 @@ __global__ __launch_bounds__(kGemmThreads, (TB <= 2 && kStages <= 3) ? 2 : 1) vo
     static_for<kPeriod>([&](auto p_tag) { slab(p_tag, fast_tag, S0 + decltype(p_tag)::value); });
   };
   // slabs S whose last prefetch, iteration S*kSlabIters + kSlabIters - 1 + kStages - 1, is in range
-  const int n_steady = n_iter >= kSlabIters + kStages - 1 ? (n_iter - kStages + 1) / kSlabIters : 0;
+  const int n_steady = n_iter_w >= kSlabIters + kStages - 1 ? (n_iter_w - kStages + 1) / kSlabIters : 0;
   int s = 0;
   for (; s + kPeriod <= n_steady; s += kPeriod) period(std::true_type{}, s);
   for (; s < n_slab; s += kPeriod) period(std::false_type{}, s);
@@ -545,7 +547,24 @@ template <typename T>
 static hipError_t launch_t(GemmArgs a, hipStream_t st) {
   a.m_tiles = (a.m + 127) / 128;
   const int tb = a.m_tiles > 1 ? 4 : (a.m + 31) / 32;
-  a.grid_x = (a.total_blocks + kGemmWaves - 1) / kGemmWaves;
+  // Workgroups along the rows.  A compute unit sustains about 30 GB/s whatever the number of its waves, so what counts is
+  // the largest number of blocks any workgroup streams.  With four blocks per workgroup the launch may leave compute
+  // units idle (7B gate/up: 688 blocks = 172 workgroups); if the blocks fit in three, two or one per workgroup on at
+  // most 256 workgroups (all splits together), the launch takes that form: wave w streams block x + w * grid_x and
+  // the waves left without a block only help to stage the X slab (7B gate/up 36.1 -> 33.6 us, O 10.8 -> 10.0, down with
+  // 4 splits 24.3 -> 20.3).  Otherwise four adjacent blocks per workgroup: spreading without lowering the largest count
+  // measured 1 - 4 % slower at the 13B shapes.
+  {
+    const int cap = std::max(1, 256 / a.n_split);
+    const int per_wg = (a.total_blocks + cap - 1) / cap;
+    if (per_wg < kGemmWaves) {
+      a.grid_x = (a.total_blocks + per_wg - 1) / per_wg;
+      a.blk_per_wg = 1; a.blk_per_wave = a.grid_x;
+    } else {
+      a.grid_x = (a.total_blocks + kGemmWaves - 1) / kGemmWaves;
+      a.blk_per_wg = kGemmWaves; a.blk_per_wave = 1;
+    }
+  }
   // SwiGLU mode: the one gate/up matrix, 16 columns per block, whole K (the activation is not linear)
   if (a.act != nullptr && (a.nseg != 1 || a.n_split != 1 || a.seg_blocks[0] != (a.seg_rows[0] + 15) / 16)) return hipErrorInvalidValue;
   dim3 grid(a.grid_x, a.n_split);

@@ -44,11 +44,12 @@ struct GemmArgs {
   int nseg, total_blocks;
   float *part;  int ldp;  int m_pad;    // partial sums [n_split][m_pad][ldp], fp32
   int n_split;                          // K is cut into n_split ranges of whole slabs, balanced to one slab
-  // SwiGLU mode (act != nullptr): exactly two segments, gate and up, of seg_rows[0] rows each, n_split = 1.
-  // A workgroup then owns two gate blocks and the SAME two up blocks and writes
+  // SwiGLU mode (act != nullptr): one segment, the packed gate/up matrix; seg_rows[0] = columns of act,
+  // seg_blocks[0] = ceil(columns / 16), n_split = 1.  The wave that streams a block writes
   // act[i][c] = silu(gate) * up in the storage type instead of partial sums.
   void *act;
   int m_tiles, grid_x;                  // set by launch_gemm: 128-row tiles of X, workgroups per tile and split
+  int blk_per_wg, blk_per_wave;         // set by launch_gemm: wave w of workgroup x streams block x * blk_per_wg + w * blk_per_wave
 };
 hipError_t launch_gemm(int dtype, const GemmArgs &a, hipStream_t st);
 hipError_t gemm_init();                 // one-time kernel attributes; call outside any stream capture
