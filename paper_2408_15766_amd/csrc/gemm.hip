@@ -26,7 +26,9 @@
 // contiguous, which is harmless because A and B are indexed by the same (g, element) pair.
 //
 // Each wave owns one 32-row block of W for the workgroup's K range and all
-// token blocks; the four waves of a workgroup share the X slab.  Weight loads
+// token blocks; the four waves of a workgroup share the X slab.  Which blocks a
+// workgroup takes is the launch's choice (four adjacent ones, or fewer, spread so
+// that every compute unit has a workgroup: launch_t).  Weight loads
 // run kStages - 1 iterations ahead through a register ring; the X slab is
 // double-buffered in LDS and prefetched one slab ahead through registers.
 //
@@ -588,7 +590,6 @@ static hipError_t launch_t(GemmArgs a, hipStream_t st) {
 
 int gemm_k_per_iter(int dtype) { return dtype == 1 ? 128 : 64; }
 int gemm_k_per_slab(int dtype) { return kSlabIters * gemm_k_per_iter(dtype); }
-int gemm_rows_per_group() { return 32 * kGemmWaves; }
 
 hipError_t launch_gemm(int dtype, const GemmArgs &a, hipStream_t st) {
   { hipError_t e = gemm_init(); if (e != hipSuccess) return e; }

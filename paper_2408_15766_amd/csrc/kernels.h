@@ -55,7 +55,6 @@ hipError_t launch_gemm(int dtype, const GemmArgs &a, hipStream_t st);
 hipError_t gemm_init();                 // one-time kernel attributes; call outside any stream capture
 int gemm_k_per_slab(int dtype);
 int gemm_k_per_iter(int dtype);
-int gemm_rows_per_group();
 // Packed layout of a row-major [rows, in] matrix (see gemm.hip): size in bytes, and the out-of-place repack.
 size_t packed_weight_bytes(int dtype, int rows, int in);
 hipError_t launch_pack_weight(int dtype, const void *src, int rows, int in, void *dst, hipStream_t st);
