@@ -156,7 +156,6 @@ __global__ __launch_bounds__(kGemmThreads, (TB <= 2 && kStages <= 3) ? 2 : 1) vo
   const int row = (blk - b0) * 32 + c;
 
   // K splits are balanced to within one slab: split y covers slabs [y*S/n, (y+1)*S/n)
-  constexpr int KSLAB = kSlabRowBytes / (int)sizeof(T);
   const int n_it_total = (a.in + KI - 1) / KI;                         // tiles along k (K zero-padded to KI)
   const int n_slabs_total = (n_it_total + kSlabIters - 1) / kSlabIters;
   const int it_begin = (int)((long long)by * n_slabs_total / a.n_split) * kSlabIters;
@@ -310,7 +309,6 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_tiled_kernel(GemmArgs a)
   const int unit = bx * kGemmWaves + wave;                     // pair of consecutive blocks
   bool active[WB]; int seg_rows[WB], seg_col0[WB], row[WB], blk_of[WB];
   const char *wstream[WB];
-  constexpr int KSLAB = kSlabRowBytes / (int)sizeof(T);
   const int n_it_total = (a.in + KI - 1) / KI;
   const int n_slabs_total = (n_it_total + kSlabIters - 1) / kSlabIters;
   const int it_begin = (int)((long long)by * n_slabs_total / a.n_split) * kSlabIters;
